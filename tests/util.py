@@ -1,0 +1,56 @@
+"""Helpers shared by the tests: oracle layers from workload tensors, acceptance checks."""
+import numpy as np
+
+from oracle import pf_oracle
+from paper_2312_12456_amd import workload as wl
+
+# Acceptance bar for fp16 weights with fp32 accumulation against the fp64 oracle.
+MAX_ABS = 2e-2
+MAX_REL = 1e-2
+SCORE_BAND = 1e-3
+
+
+def oracle_layer(cfg, host, threshold=None):
+    """pf_oracle.Layer over the numpy tensors of workload.to_host(make_layer(...))."""
+    return pf_oracle.Layer(
+        cfg.d, cfg.ffn, cfg.r, act=cfg.act, wtype=cfg.wtype,
+        threshold=cfg.threshold if threshold is None else threshold,
+        w_up=host.get("w_up"), w_gate=host.get("w_gate"), w_down=host.get("w_down"),
+        s_up=host.get("s_up"), s_gate=host.get("s_gate"), s_down=host.get("s_down"),
+        b_up=host.get("b_up"), b_down=host.get("b_down"), p1=host.get("p1"), p2=host.get("p2"),
+        p_bias=host.get("p_bias"))
+
+
+def small_cfg(name="t", d=256, ffn=512, r=64, act=wl.ACT_RELU, wtype=wl.W_FP16, rate=0.1,
+              alpha=1.2, layers=1):
+    return wl.StackConfig(name, layers, d, ffn, r, act, wtype, rate, alpha, 8, (1,))
+
+
+def check_output(y_dev, y_ref, what=""):
+    """max-abs <= 2e-2 and max-abs / max|ref| <= 1e-2."""
+    y_dev = np.asarray(y_dev, dtype=np.float64)
+    y_ref = np.asarray(y_ref, dtype=np.float64)
+    assert y_dev.shape == y_ref.shape, (y_dev.shape, y_ref.shape)
+    assert np.isfinite(y_dev).all(), what
+    err = float(np.max(np.abs(y_dev - y_ref))) if y_ref.size else 0.0
+    scale = float(np.max(np.abs(y_ref))) if y_ref.size else 0.0
+    assert err <= MAX_ABS, "%s max-abs %.3e" % (what, err)
+    if scale > 0:
+        assert err / scale <= MAX_REL, "%s rel %.3e" % (what, err / scale)
+    return err
+
+
+def check_active_set(dev_mask, ref_scores, threshold, what=""):
+    """Bit-exact union mask outside the 1e-3 score band around the threshold."""
+    ref_scores = np.atleast_2d(ref_scores)
+    ref_rows = ref_scores > threshold
+    ref_mask = ref_rows.any(axis=0)
+    # a neuron is comparable if no token's score sits in the band, or some token
+    # outside the band already decides it active
+    in_band = np.abs(ref_scores - threshold) < SCORE_BAND
+    decided_on = (ref_rows & ~in_band).any(axis=0)
+    comparable = decided_on | ~in_band.any(axis=0)
+    bad = comparable & (np.asarray(dev_mask, bool) != ref_mask)
+    assert not bad.any(), "%s: %d active-set mismatches outside the band, first %s" % (
+        what, int(bad.sum()), np.flatnonzero(bad)[:8])
+    return int((~comparable).sum())
