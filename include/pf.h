@@ -1,0 +1,162 @@
+/*
+ * pf.h -- C ABI of libpf: the neuron-aware sparse FFN of one LLM decode step on one
+ * MI355X (gfx950), after PowerInfer (arXiv 2312.12456).
+ *
+ * The paper's problem statement for one layer (Sec. 4.2 single-layer example, Sec. 5.1
+ * predictors, Sec. 5.4 neuron-aware operators): a hidden state comes in; a small MLP
+ * predictor marks the FFN neurons expected to fire; only for those neurons the FC1 row
+ * (and gate row), the activation and the FC2 column are read and computed; the FFN
+ * output goes out.  Everything here runs on the GPU (no CPU half, no merge step): the
+ * whole model is resident in HBM.
+ *
+ * Conventions
+ *  - Every data pointer is a DEVICE pointer unless a comment says "host".  Pointers
+ *    passed in pf_layer_weights are BORROWED: the library keeps them and the caller
+ *    keeps the memory alive and unchanged until pf_layer_destroy.  The library owns
+ *    only its per-context scratch.
+ *  - Row-major, neuron-major: one neuron of FC1, of the gate matrix and of FC2 is one
+ *    contiguous run.  FC2 is therefore passed transposed, [ffn][d].
+ *  - All compute calls are asynchronous on `stream` (a hipStream_t passed as void*,
+ *    NULL = the default stream), never synchronise with the host and never copy the
+ *    active count back: the sparse kernels size their work from device memory.
+ *  - A pf_ctx (its scratch) may be used by one stream at a time.
+ *  - Every function returns a pf_status; nothing throws, exits or prints.  Argument
+ *    errors are detected on the host before anything is launched.
+ */
+#ifndef PF_H
+#define PF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PF_OK = 0,
+    PF_EINVAL = 1,       /* null pointer, negative size, batch above the context's limit */
+    PF_ESHAPE = 2,       /* ffn % 64, d % 8, r % 8, (int4) d % 128, layer larger than ctx */
+    PF_ENOMEM = 3,       /* device or host allocation failed                             */
+    PF_EHIP = 4,         /* a HIP call failed; pf_last_error has its text                */
+    PF_EUNSUPPORTED = 5  /* activation / weight type combination not built               */
+} pf_status;
+
+typedef enum {
+    PF_ACT_RELU = 0,  /* OPT-style: h = ReLU(w_up.x + b_up)                      (Sec. 2.1) */
+    PF_ACT_REGLU = 1  /* ReLU-gated: h = ReLU(w_gate.x + b_up) * (w_up.x)  (Table "model_eval") */
+} pf_act;
+
+typedef enum {
+    PF_W_FP16 = 0,      /* IEEE binary16 weights                                  (Sec. 8.1) */
+    PF_W_INT4_G128 = 1  /* nibble u in [0,15], value = scale * (u - 8), one fp16 scale per
+                           128 consecutive elements of a neuron's row; element 2j in the low
+                           nibble of byte j, 2j+1 in the high nibble             (Sec. 8.1) */
+} pf_wtype;
+
+typedef struct {
+    int32_t d;          /* model width                      */
+    int32_t ffn;        /* neurons in the FFN block         */
+    int32_t r;          /* predictor hidden width           */
+    int32_t act;        /* pf_act                           */
+    int32_t wtype;      /* pf_wtype (predictor is always fp16) */
+    float threshold;    /* predictor score threshold in (0,1): active iff score > threshold */
+} pf_layer_desc;
+
+typedef struct {
+    const void *w_up;    /* [ffn][d] fp16, or [ffn][d/2] packed int4                     */
+    const void *w_gate;  /* same shape; NULL unless act == PF_ACT_REGLU                  */
+    const void *w_down;  /* FC2 transposed, [ffn][d] / [ffn][d/2]                        */
+    const void *s_up;    /* [ffn][d/128] fp16 scales, int4 only, else NULL               */
+    const void *s_gate;
+    const void *s_down;
+    const float *b_up;   /* [ffn] FC1 bias (the gate bias when gated) or NULL            */
+    const float *b_down; /* [d] FC2 bias or NULL                                         */
+    const void *p1;      /* [r][d]   fp16 predictor input layer                          */
+    const void *p2;      /* [ffn][r] fp16 predictor output layer                         */
+    const float *p_bias; /* [ffn] added to the predictor logit, or NULL                  */
+} pf_layer_weights;
+
+typedef struct pf_ctx pf_ctx;
+typedef struct pf_layer pf_layer;
+typedef struct pf_plan pf_plan;
+
+/* Context: binds a device and owns scratch sized for the given maxima (hidden vector,
+ * mask words, index list, FC1 outputs, FC2 partial sums).  `device` is a HIP ordinal.
+ * Errors: PF_EINVAL (out == NULL, sizes < 1, max_batch > 8), PF_ESHAPE, PF_ENOMEM, PF_EHIP. */
+pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int max_r,
+                        int max_batch);
+void pf_ctx_destroy(pf_ctx *ctx);
+
+/* Layer: validates the descriptor against the context and records the borrowed weight
+ * pointers (nothing is copied or launched).  p1/p2 may be NULL for a layer that is only
+ * used with pf_sparse_ffn. */
+pf_status pf_layer_create(pf_ctx *ctx, const pf_layer_desc *desc, const pf_layer_weights *w,
+                          pf_layer **out);
+void pf_layer_destroy(pf_layer *layer);
+
+/* Activation predictor (Sec. 5.1: input, one hidden, output layer):
+ *   t = ReLU(p1 . x),  logit = p2 . t + p_bias,  score = 1/(1+exp(-logit)),
+ *   neuron i is active iff score_i > threshold for at least one of the B tokens.
+ * x [B][d] fp32.  scores: optional [B][ffn] fp32 (NULL to skip).  mask_words: [ffn/64]
+ * uint64, bit b of word w = neuron 64*w + b.  The comparison is made on the fp32 logit
+ * against logit(threshold), which is the same decision in exact arithmetic. */
+pf_status pf_predict(pf_ctx *ctx, const pf_layer *layer, const float *x, int B, float *scores,
+                     uint64_t *mask_words, void *stream);
+
+/* Active-index compaction: idx[0..count) = ascending positions of the set bits of
+ * mask_words[0..ffn/64), *count = their number (a device int32).  idx has capacity ffn;
+ * entries from count on are left unspecified.  (The paper tests activation inside every
+ * thread block, Sec. 5.4; compacting first is this library's choice for a 256-CU part.) */
+pf_status pf_compact(pf_ctx *ctx, const uint64_t *mask_words, int ffn, int32_t *idx,
+                     int32_t *count, void *stream);
+
+/* Neuron-aware FFN over an index list (Sec. 5.4; Sec. 2.1 for the block itself):
+ *   for j < *count, i = idx[j]:  h_j = act(row i of FC1 (and gate) . x + b_up[i])
+ *   y[b][:] = b_down + sum_j h_j[b] * (row i of FC2^T)
+ * for every token b of the batch (the list is the union over the batch, Sec. 8.2).
+ * idx: ascending, no duplicates, entries in [0, ffn) (out-of-range entries are skipped);
+ * count: device int32, clamped to [0, ffn].  y [B][d] fp32 is fully overwritten, also
+ * when *count == 0 (then y = b_down).  Accumulation is fp32, in a fixed order. */
+pf_status pf_sparse_ffn(pf_ctx *ctx, const pf_layer *layer, const float *x, int B,
+                        const int32_t *idx, const int32_t *count, float *y, void *stream);
+
+/* One layer of the decode step: predict -> compact -> sparse FFN, on one stream with no
+ * host involvement (Sec. 4.2 without the CPU half).  x [B][d] -> y [B][d]. */
+pf_status pf_layer_step(pf_ctx *ctx, const pf_layer *layer, const float *x, int B, float *y,
+                        void *stream);
+
+/* Device pointers to the mask words, index list and count left by the last
+ * pf_layer_step on this context (valid until the next compute call; for tests and
+ * for an activation profiler in the sense of Sec. 6.1). */
+pf_status pf_ctx_last_active(pf_ctx *ctx, const uint64_t **mask_words, const int32_t **idx,
+                             const int32_t **count);
+
+/* Glue of the synthetic FFN stack used for benchmarking (not in the paper): residual add
+ * and scale-only RMS normalisation, x_next = (x + y) * sqrt(d) / ||x + y||_2 per token. */
+pf_status pf_stack_glue(pf_ctx *ctx, const float *x, const float *y, int d, int B,
+                        float *x_next, void *stream);
+
+/* One decode step of a whole FFN stack: for each layer, pf_layer_step then pf_stack_glue.
+ * layers: HOST array of n_layers layer handles of equal d.  x [B][d] in, x_out [B][d]
+ * out (may alias x). */
+pf_status pf_stack_step(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x,
+                        int B, float *x_out, void *stream);
+
+/* The same step recorded once into a HIP graph and replayed: removes per-kernel launch
+ * cost from the token loop.  x and x_out are fixed at creation; each pf_plan_run reads x
+ * and writes x_out.  The plan borrows ctx and the layers. */
+pf_status pf_plan_create(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x,
+                         int B, float *x_out, void *stream, pf_plan **out);
+pf_status pf_plan_run(pf_plan *plan, void *stream);
+void pf_plan_destroy(pf_plan *plan);
+
+const char *pf_strerror(pf_status s);
+/* Text of the last error on this context (host string, valid until the next call). */
+const char *pf_last_error(const pf_ctx *ctx);
+/* Library version string (host). */
+const char *pf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PF_H */
