@@ -18,7 +18,8 @@ namespace {
 
 constexpr int kMaxBatch = 8;
 constexpr int kChunksCap = 128;         // upper bound of neuron chunks in the FC2 kernel
-constexpr int kLdsBudget = 160 * 1024;  // LDS per workgroup on gfx950
+constexpr int kLdsMax = 160 * 1024;     // LDS per workgroup on gfx950
+constexpr int kLdsDefault = 64 * 1024;  // what a kernel may use without opting in
 
 }  // namespace
 
@@ -29,6 +30,7 @@ struct pf_ctx {
     int down_chunks = 64;    // grid.y of the FC2 kernel
     int down_min_rows = 16;  // least neurons per chunk
     int up_grid_cap = 2048;
+    int lds_budget = kLdsDefault;  // dynamic LDS a kernel of this context may request
     // scratch (device)
     float *t = nullptr;             // [max_batch][max_r] predictor hidden vector
     uint64_t *mask_words = nullptr; // [max_ffn / 64]
@@ -80,9 +82,9 @@ inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 inline int kpad_of(int k) { return cdiv(k, pf::kChunk) * pf::kChunk; }
 
 // Largest batch tile whose staged activations ([tile][kpad] fp32) fit the LDS budget.
-inline int batch_tile(int k, int B)
+inline int batch_tile(const pf_ctx *ctx, int k, int B)
 {
-    int fit = kLdsBudget / (kpad_of(k) * 4);
+    int fit = ctx->lds_budget / (kpad_of(k) * 4);
     if (fit > kMaxBatch) fit = kMaxBatch;
     return fit < B ? fit : B;
 }
@@ -104,7 +106,7 @@ template <typename K>
 hipError_t allow_lds(K kernel)
 {
     return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsMax);
 }
 
 template <int B>
@@ -148,7 +150,7 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, int B, 
     const __half *p1 = static_cast<const __half *>(L->w.p1);
     const __half *p2 = static_cast<const __half *>(L->w.p2);
     // hidden layer, in batch tiles that fit LDS
-    const int tile = batch_tile(D.d, B);
+    const int tile = batch_tile(ctx, D.d, B);
     for (int b0 = 0; b0 < B; b0 += tile) {
         const int bt = (B - b0) < tile ? (B - b0) : tile;
         const size_t lds = (size_t)bt * kpad_of(D.d) * sizeof(float);
@@ -183,7 +185,7 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     const __half *w_up = static_cast<const __half *>(L->w.w_up);
     const __half *w_gate = static_cast<const __half *>(L->w.w_gate);
     const __half *w_down = static_cast<const __half *>(L->w.w_down);
-    const int tile = batch_tile(D.d, B);
+    const int tile = batch_tile(ctx, D.d, B);
     int up_grid = cdiv(D.ffn, pf::kUpWaves);
     if (up_grid > ctx->up_grid_cap) up_grid = ctx->up_grid_cap;
     for (int b0 = 0; b0 < B; b0 += tile) {
@@ -262,8 +264,9 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
     if (max_d < 1 || max_ffn < 1 || max_r < 1 || max_batch < 1 || max_batch > kMaxBatch || device < 0)
         return PF_EINVAL;
     if (max_ffn % 64 != 0 || max_d % 8 != 0 || max_r % 8 != 0) return PF_ESHAPE;
-    if ((size_t)max_batch * kpad_of(max_r) * sizeof(float) > 64 * 1024 ||
-        (size_t)kpad_of(max_d) * sizeof(float) > (size_t)kLdsBudget)
+    // the staged hidden vector of the whole batch and one staged token must fit LDS
+    if ((size_t)max_batch * kpad_of(max_r) * sizeof(float) > (size_t)kLdsDefault - 16 * 1024 ||
+        (size_t)kpad_of(max_d) * sizeof(float) > (size_t)kLdsDefault)
         return PF_ESHAPE;
     pf_ctx *ctx = new (std::nothrow) pf_ctx();
     if (!ctx) return PF_ENOMEM;
@@ -298,8 +301,13 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
             int c = atoi(v);
             if (c >= 1 && c <= 65535) ctx->up_grid_cap = c;
         }
-        e = allow_lds_all();
-        if (e != hipSuccess) { st = PF_EHIP; break; }
+        // larger staged batches need the opt-in LDS size; without it batches are tiled smaller
+        if (prop.sharedMemPerBlock >= (size_t)kLdsMax || prop.maxSharedMemoryPerMultiProcessor >= (size_t)kLdsMax) {
+            if (allow_lds_all() == hipSuccess)
+                ctx->lds_budget = kLdsMax;
+            else
+                (void)hipGetLastError();
+        }
 #define PF_ALLOC(ptr, bytes)                                                  \
         e = hipMalloc(reinterpret_cast<void **>(&(ptr)), (bytes));            \
         if (e != hipSuccess) { st = e == hipErrorOutOfMemory ? PF_ENOMEM : PF_EHIP; break; }

@@ -231,7 +231,7 @@ def test_stack_step_teacher_forced_and_plan_replay(pf, oracle):
         torch.cuda.synchronize()
         wptr, _, _ = ctx.last_active()
         words = torch.empty(cfg.ffn // 64, dtype=torch.int64, device="cuda")
-            pf.copy_from_device_address(words, wptr)
+        pf.copy_from_device_address(words, wptr)
         mask = _words_to_mask(words, cfg.ffn)
         check_active_set(mask, Os[l].predict(xo)["scores"], cfg.threshold, "stack layer %d" % l)
         y_ref = Os[l].masked_ffn(xo, mask)
