@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Decode FFN-stack benchmark for the neuron-aware sparse FFN library (one MI355X).
+
+One "step" is one decode token pushed through the whole FFN stack of the configured model
+shape: per layer predictor -> compaction -> row-sparse FC1 -> column-sparse FC2 -> glue
+(residual + scale-only RMS norm).  Weights and all token inputs are resident in HBM before
+the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config opt-6.7b] [--batch B]
+
+Three legs:
+  value         K tokens through the recorded HIP graph of the stack (timed with host clocks
+                between device synchronisations);
+  roofline      a second, eager pass in which the library brackets every kernel launch with
+                HIP events on its stream; the dominant kernel's algorithmic bytes per launch
+                over its mean duration against the 8 TB/s HBM peak;
+  cpu_baseline  the CPU oracle timed on the host cores on a bounded sample of the same
+                workload (a few layers x a few tokens, scaled by the layer count).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="decode tokens timed (default: config)")
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", default="opt-6.7b")
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--layers", type=int, default=None, help="override the layer count")
+    ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
+    ap.add_argument("--profile-steps", type=int, default=16)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--cpu-layers", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-pred-bias", action="store_true",
+                    help="bias-free random predictor (about half of the neurons marked)")
+    ap.add_argument("--seed", type=int, default=2312)
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2312_12456_amd import pf
+    from paper_2312_12456_amd import workload as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    cfg = wl.CONFIGS[args.config]
+    if args.layers:
+        cfg = wl.scaled(cfg, layers=args.layers)
+    B = args.batch
+    K = args.steps if args.steps is not None else cfg.tokens
+    W = args.warmup
+    dev = "cuda"
+
+    # ---- workload resident in HBM ---------------------------------------------------
+    t_gen = time.time()
+    ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
+    tensors, layers = [], []
+    for l in range(cfg.layers):
+        t = wl.make_layer(cfg, l, args.seed, device=dev, pred_bias=not args.no_pred_bias)
+        tensors.append(t)
+        layers.append(pf.Layer.from_workload(ctx, cfg, t))
+    n_tok = max(K, W, args.profile_steps)
+    x_all = torch.stack([wl.make_inputs(cfg, t, args.seed, batch=B) for t in range(n_tok)]).to(dev)
+    x_buf = torch.empty((B, cfg.d), device=dev)
+    out = torch.empty((B, cfg.d), device=dev)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+
+    plan = pf.Plan(ctx, layers, x_buf, out) if args.mode == "graph" else None
+
+    def step(t):
+        x_buf.copy_(x_all[t % n_tok])
+        if plan is not None:
+            plan.run()
+        else:
+            ctx.stack_step(layers, x_buf, out)
+
+    for t in range(W):
+        step(t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(K):
+        step(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert bool(torch.isfinite(out).all()), "non-finite stack output"
+    ms_per_step = 1e3 * elapsed / K
+    tokens_per_s = B * K / elapsed
+
+    # ---- per-kernel pass: HIP events around every launch, active counts read back ----
+    P = max(1, min(args.profile_steps, n_tok))
+    counts = np.zeros((P, cfg.layers), dtype=np.int64)
+    y = torch.empty((B, cfg.d), device=dev)
+    xa = torch.empty((B, cfg.d), device=dev)
+    cnt = torch.empty(1, dtype=torch.int32, device=dev)
+    _, _, count_ptr = ctx.last_active()
+    ctx.profile_begin()
+    for t in range(P):
+        xa.copy_(x_all[t])
+        for l, L in enumerate(layers):
+            ctx.layer_step(L, xa, y)
+            ctx.stack_glue(xa, y, xa)
+            pf.copy_from_device_address(cnt, count_ptr)
+            counts[t, l] = int(cnt.item())
+    stats = ctx.profile_end()
+    k_mean = float(counts.mean())
+    nm = cfg.n_matrices
+    alg_bytes = {
+        "k_pred_hidden": 2.0 * cfg.r * cfg.d,
+        "k_pred_out": 2.0 * cfg.ffn * cfg.r + (0 if args.no_pred_bias else 4.0 * cfg.ffn),
+        "k_up": k_mean * (nm - 1) * cfg.row_bytes,
+        "k_down": k_mean * cfg.row_bytes,
+    }
+    kernels = {}
+    for name, (launches, total_ms) in stats.items():
+        if launches == 0:
+            continue
+        avg_us = 1e3 * total_ms / launches
+        ent = {"launches": launches, "avg_us": round(avg_us, 3)}
+        if name in alg_bytes:
+            ent["alg_bytes"] = alg_bytes[name]
+            ent["GBps"] = round(alg_bytes[name] / (avg_us * 1e-6) / 1e9, 1)
+        kernels[name] = ent
+    dominant = max((n for n in kernels if n in alg_bytes), key=lambda n: stats[n][1])
+    dk = kernels[dominant]
+    roofline = {
+        "bound": "hbm", "kernel": dominant, "achieved": dk["GBps"], "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s", "frac": round(dk["GBps"] / HBM_PEAK_GBPS, 4), "traffic": None,
+        "alg_bytes_per_launch": dk["alg_bytes"], "avg_us": dk["avg_us"],
+    }
+    touched = k_mean * nm * cfg.row_bytes
+    t_sparse_us = kernels["k_up"]["avg_us"] + kernels["k_down"]["avg_us"]
+    touched_gbps = touched / (t_sparse_us * 1e-6) / 1e9
+
+    # ---- CPU oracle on the host cores, bounded sample --------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import pf_oracle
+        ns = min(args.cpu_layers, cfg.layers)
+        ol = []
+        for l in range(ns):
+            h = wl.to_host(tensors[l])
+            ol.append(pf_oracle.Layer(
+                cfg.d, cfg.ffn, cfg.r, act=cfg.act, wtype=cfg.wtype, threshold=cfg.threshold,
+                w_up=h.get("w_up"), w_gate=h.get("w_gate"), w_down=h.get("w_down"),
+                s_up=h.get("s_up"), s_gate=h.get("s_gate"), s_down=h.get("s_down"),
+                b_up=h.get("b_up"), b_down=h.get("b_down"), p1=h.get("p1"), p2=h.get("p2"),
+                p_bias=h.get("p_bias")))
+        xs_host = x_all[:min(n_tok, 64)].cpu().numpy()
+        layer_calls, t_cpu, tok = 0, 0.0, 0
+        while t_cpu < args.cpu_seconds:
+            xh = xs_host[tok % xs_host.shape[0]]
+            c0 = time.perf_counter()
+            for O in ol:
+                yh = O.layer_step(xh)
+                xh = pf_oracle.stack_glue(xh, yh)
+            t_cpu += time.perf_counter() - c0
+            layer_calls += ns
+            tok += 1
+        per_layer = t_cpu / layer_calls
+        cpu = {
+            "value": round(B / (per_layer * cfg.layers), 4), "unit": "tokens/s",
+            "cores": pf_oracle.num_threads(), "kind": "oracle",
+            "sample": "%d tokens x first %d of %d layers at full shape, fp64 oracle layer_step + "
+                      "glue, %.1f s; per-layer time scaled by the layer count"
+                      % (tok, ns, cfg.layers, t_cpu),
+        }
+
+    result = {
+        "metric": "decode FFN-stack tokens/s at batch %d" % B,
+        "value": round(tokens_per_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s FFN stack: %d layers, d=%d, ffn=%d, r=%d, %s, %s weights, "
+                               "batch %d, Zipf(%.1f) mean rate %.0f%%, %d decode tokens"
+                               % (cfg.name, cfg.layers, cfg.d, cfg.ffn, cfg.r,
+                                  "ReGLU" if cfg.act == wl.ACT_REGLU else "ReLU",
+                                  "int4-g128" if cfg.wtype == wl.W_INT4_G128 else "fp16",
+                                  B, cfg.alpha, 100 * cfg.rate, K),
+                   "launch": args.mode, "predictor_bias": not args.no_pred_bias},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "touched": {"k_mean": round(k_mean, 1), "active_frac": round(k_mean / cfg.ffn, 4),
+                    "bytes_per_layer": touched, "sparse_us_per_layer": round(t_sparse_us, 3),
+                    "GBps": round(touched_gbps, 1), "frac_of_peak": round(touched_gbps / HBM_PEAK_GBPS, 4)},
+        "kernels": kernels,
+        "setup_s": round(t_gen, 1),
+    }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -150,6 +150,20 @@ pf_status pf_plan_create(pf_ctx *ctx, pf_layer *const *layers, int n_layers, con
 pf_status pf_plan_run(pf_plan *plan, void *stream);
 void pf_plan_destroy(pf_plan *plan);
 
+/* Per-kernel timing for measurement.  Between pf_profile_begin and pf_profile_end every
+ * kernel the library launches eagerly on this context (not inside a recorded plan) is
+ * bracketed by a pair of HIP events on its own stream, up to 32768 launches.
+ * pf_profile_end waits for the recorded events (the only call here that synchronises with
+ * the host) and fills one entry per kernel: name (host string), launches, summed ms.
+ * stats: HOST array of `capacity` >= 6 entries; *n_out receives the number filled. */
+typedef struct {
+    const char *name;
+    uint64_t launches;
+    double total_ms;
+} pf_kernel_stat;
+pf_status pf_profile_begin(pf_ctx *ctx);
+pf_status pf_profile_end(pf_ctx *ctx, pf_kernel_stat *stats, int capacity, int *n_out);
+
 const char *pf_strerror(pf_status s);
 /* Text of the last error on this context (host string, valid until the next call). */
 const char *pf_last_error(const pf_ctx *ctx);

@@ -6,32 +6,86 @@
 //   compact: idx[] = ascending positions of the set bits, count = popcount
 // Both GEMVs are HBM-bound streams of fp16 rows: one wave per row, 16-byte loads per
 // lane, activations staged once per workgroup in LDS, fp32 accumulation, DPP reduction.
+// No kernel here uses device-scope fences: data crosses workgroups only at kernel ends.
 #pragma once
 #include "dev_util.h"
 
 namespace pf {
 
 constexpr int kPredThreads = 256;  // 4 waves per workgroup
+constexpr int kPredWaves = kPredThreads / kWave;
 
 // ---------------------------------------------------------------------------------------
 // Hidden layer.  grid = ceil(r / 4); wave w of block g owns row 4g + w.
-template <int B>
+// With GLUE the input of the layer is formed on the fly from the previous layer's input and
+// FFN output, x = (xp + yp) * sqrt(d) / ||xp + yp||_2 per token (the stack's residual +
+// scale-only RMS norm): every block stages v = xp + yp, reduces ||v||^2 itself and applies
+// the scale to its dot products; block 0 also writes x for the kernels that follow.
+template <int B, bool GLUE>
 __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__restrict__ p1,
                                                               const float *__restrict__ x,
+                                                              const float *__restrict__ yp,
+                                                              float *__restrict__ x_new,
                                                               float *__restrict__ t, int d, int r)
 {
     extern __shared__ float xs[];
+    __shared__ float ss_w[kPredWaves][B];
     constexpr int U = 8;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nch = (d + kChunk - 1) / kChunk, kpad = nch * kChunk;
-    const int m = blockIdx.x * (kPredThreads / kWave) + wave;
+    const int m = blockIdx.x * kPredWaves + wave;
     const bool live = m < r;
     const __half *row = p1 + (size_t)(live ? m : 0) * d;
 
     WGroup<U> g;
     load_group<U>(g, row, live ? d : 0, 0, lane);  // in flight while x is staged
-    stage_vector<B>(xs, x, d, kpad);
-    __syncthreads();
+    float scale[B];
+    if (GLUE) {
+        float ss[B];
+#pragma unroll
+        for (int b = 0; b < B; ++b) ss[b] = 0.f;
+        for (int e = threadIdx.x * 4; e < kpad; e += kPredThreads * 4) {
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (e < d) {
+                    const float4 a = *reinterpret_cast<const float4 *>(x + (size_t)b * d + e);
+                    const float4 c = *reinterpret_cast<const float4 *>(yp + (size_t)b * d + e);
+                    v = make_float4(a.x + c.x, a.y + c.y, a.z + c.z, a.w + c.w);
+                }
+                ss[b] = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss[b]))));
+                *reinterpret_cast<float4 *>(xs + b * kpad + lds_slot(e)) = v;
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            const float s = wave_sum(ss[b]);
+            if (lane == 0) ss_w[wave][b] = s;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            float tot = 0.f;
+#pragma unroll
+            for (int k = 0; k < kPredWaves; ++k) tot += ss_w[k][b];
+            scale[b] = tot > 0.f ? sqrtf((float)d / tot) : 0.f;
+        }
+        if (blockIdx.x == 0) {
+            for (int e = threadIdx.x * 4; e < d; e += kPredThreads * 4) {
+#pragma unroll
+                for (int b = 0; b < B; ++b) {
+                    const float4 v = *reinterpret_cast<const float4 *>(xs + b * kpad + lds_slot(e));
+                    *reinterpret_cast<float4 *>(x_new + (size_t)b * d + e) =
+                        make_float4(v.x * scale[b], v.y * scale[b], v.z * scale[b], v.w * scale[b]);
+                }
+            }
+        }
+    } else {
+        stage_vector<B>(xs, x, d, kpad);
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < B; ++b) scale[b] = 1.f;
+    }
 
     float acc[B];
 #pragma unroll
@@ -43,99 +97,29 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
     }
 #pragma unroll
     for (int b = 0; b < B; ++b) {
-        const float s = wave_sum(acc[b]);
+        const float s = wave_sum(acc[b]) * scale[b];
         if (live && lane == 0) t[(size_t)b * r + m] = fmaxf(s, 0.f);
     }
 }
 
 // ---------------------------------------------------------------------------------------
-// Compaction of mask words into an ascending index list, by one workgroup of NT threads.
-// Pass 1: per-word popcount and a block-wide exclusive prefix (wave scan + LDS).
-// Pass 2: one wave per word; lane l owns bit l, its rank inside the word is the popcount
-//         of the lower bits (what a ballot + mbcnt pair would give for a live predicate).
-template <int NT>
-struct CompactLds {
-    uint64_t word[NT];
-    uint32_t pre[NT];
-    uint32_t wave_tot[NT / kWave];
-};
-
-template <int NT>
-__device__ __forceinline__ void compact_block(const uint64_t *mask_words, int nwords,
-                                              int32_t *__restrict__ idx, int32_t *__restrict__ count,
-                                              CompactLds<NT> &s)
-{
-    constexpr int NW = NT / kWave;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    uint32_t carry = 0;
-    for (int w0 = 0; w0 < nwords; w0 += NT) {
-        const int w = w0 + tid;
-        const uint64_t word = w < nwords ? mask_words[w] : 0ull;
-        const uint32_t pc = (uint32_t)__popcll(word);
-        uint32_t inc = pc;  // inclusive scan inside the wave
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t up = (uint32_t)__shfl_up((int)inc, o, 64);
-            if (lane >= o) inc += up;
-        }
-        if (lane == 63) s.wave_tot[wave] = inc;
-        s.word[tid] = word;
-        __syncthreads();
-        uint32_t before = 0, total = 0;
-#pragma unroll
-        for (int k = 0; k < NW; ++k) {
-            const uint32_t v = s.wave_tot[k];
-            if (k < wave) before += v;
-            total += v;
-        }
-        s.pre[tid] = carry + before + inc - pc;
-        __syncthreads();
-        const int nhere = min(NT, nwords - w0);
-        for (int q = wave; q < nhere; q += NW) {
-            const uint64_t wq = s.word[q];
-            const uint32_t base = s.pre[q];
-            const uint64_t below = wq & ((1ull << lane) - 1ull);
-            if ((wq >> lane) & 1ull) idx[base + (uint32_t)__popcll(below)] = (w0 + q) * 64 + lane;
-        }
-        carry += total;
-        __syncthreads();
-    }
-    if (tid == 0) *count = (int32_t)carry;
-}
-
-constexpr int kCompactThreads = 1024;
-
-__global__ __launch_bounds__(kCompactThreads) void k_compact(const uint64_t *__restrict__ mask_words,
-                                                             int nwords, int32_t *__restrict__ idx,
-                                                             int32_t *__restrict__ count)
-{
-    __shared__ CompactLds<kCompactThreads> lds;
-    compact_block<kCompactThreads>(mask_words, nwords, idx, count, lds);
-}
-
-// ---------------------------------------------------------------------------------------
 // Output layer + threshold + ballot.  grid = ffn / 64; block g (16 waves) owns neurons
-// 64g .. 64g+63, wave w of it rows 4w .. 4w+3, all in flight at once.  With FUSE the last block to
-// finish (device-scope arrival counter) also compacts the mask words, which saves a
-// launch on the layer-step path.
+// 64g .. 64g+63, wave w of it rows 4w .. 4w+3, all in flight at once; wave 0 turns the 64
+// decisions into one mask word with a ballot.
 constexpr int kPredOutThreads = 1024;
 
-template <int B, bool FUSE>
+template <int B>
 __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
     const __half *__restrict__ p2, const float *__restrict__ p_bias, const float *__restrict__ t,
-    int r, int ffn, float thr_logit, float *__restrict__ scores, uint64_t *__restrict__ mask_words,
-    unsigned int *__restrict__ arrive, int32_t *__restrict__ idx, int32_t *__restrict__ count)
+    int r, int ffn, float thr_logit, float *__restrict__ scores, uint64_t *__restrict__ mask_words)
 {
-    extern __shared__ float ts[];          // [B][kpad] staged hidden vector
+    extern __shared__ float ts[];  // [B][kpad] staged hidden vector
     __shared__ float logit_s[B][64];
-    __shared__ CompactLds<kPredOutThreads> clds;
-    __shared__ int is_last;
     // 16 waves per block leave 128 VGPRs per lane: fewer loads in flight at larger batch
-    constexpr int U = (B <= 2) ? 4 : 2, R = 4, ROWS = 64 / (kPredOutThreads / kWave);
-    static_assert(ROWS == R, "one round of R rows per wave");
+    constexpr int U = (B <= 2) ? 4 : 2, R = 64 / (kPredOutThreads / kWave);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nch = (r + kChunk - 1) / kChunk, kpad = nch * kChunk;
-    const int n0 = blockIdx.x * 64 + wave * ROWS;
+    const int n0 = blockIdx.x * 64 + wave * R;
 
     WGroup<U> g[R];
 #pragma unroll
@@ -143,35 +127,26 @@ __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
     stage_vector<B>(ts, t, r, kpad);
     __syncthreads();
 
-    for (int q0 = 0; q0 < ROWS; q0 += R) {
-        float acc[R][B];
+    float acc[R][B];
 #pragma unroll
-        for (int q = 0; q < R; ++q) {
+    for (int q = 0; q < R; ++q) {
 #pragma unroll
-            for (int b = 0; b < B; ++b) acc[q][b] = 0.f;
-            fma_group<B, U>(g[q], ts, kpad, 0, nch, lane, acc[q]);
-        }
-        for (int it0 = U; it0 < nch; it0 += U) {
+        for (int b = 0; b < B; ++b) acc[q][b] = 0.f;
+        fma_group<B, U>(g[q], ts, kpad, 0, nch, lane, acc[q]);
+    }
+    for (int it0 = U; it0 < nch; it0 += U) {
 #pragma unroll
-            for (int q = 0; q < R; ++q)
-                load_group<U>(g[q], p2 + (size_t)(n0 + q0 + q) * r, r, it0, lane);
+        for (int q = 0; q < R; ++q) load_group<U>(g[q], p2 + (size_t)(n0 + q) * r, r, it0, lane);
 #pragma unroll
-            for (int q = 0; q < R; ++q) fma_group<B, U>(g[q], ts, kpad, it0, nch, lane, acc[q]);
-        }
-        if (q0 + R < ROWS) {  // next four rows go in flight before the reductions
+        for (int q = 0; q < R; ++q) fma_group<B, U>(g[q], ts, kpad, it0, nch, lane, acc[q]);
+    }
 #pragma unroll
-            for (int q = 0; q < R; ++q)
-                load_group<U>(g[q], p2 + (size_t)(n0 + q0 + R + q) * r, r, 0, lane);
-        }
+    for (int q = 0; q < R; ++q) {
+        const float pb = p_bias ? p_bias[n0 + q] : 0.f;
 #pragma unroll
-        for (int q = 0; q < R; ++q) {
-            const int i = n0 + q0 + q;
-            const float pb = p_bias ? p_bias[i] : 0.f;
-#pragma unroll
-            for (int b = 0; b < B; ++b) {
-                const float s = wave_sum(acc[q][b]) + pb;
-                if (lane == 0) logit_s[b][wave * ROWS + q0 + q] = s;
-            }
+        for (int b = 0; b < B; ++b) {
+            const float s = wave_sum(acc[q][b]) + pb;
+            if (lane == 0) logit_s[b][wave * R + q] = s;
         }
     }
     __syncthreads();
@@ -189,20 +164,101 @@ __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
         const uint64_t word = __ballot(on);
         if (lane == 0) mask_words[blockIdx.x] = word;
     }
+}
 
-    if (FUSE) {
-        __threadfence();  // the mask word is visible device-wide before the arrival
-        if (threadIdx.x == 0) {
-            const unsigned int prev = atomicAdd(arrive, 1u);
-            is_last = (prev == gridDim.x - 1);
-            if (is_last) *arrive = 0u;  // ready for the next launch
-        }
-        __syncthreads();
-        if (is_last) {
-            __threadfence();
-            compact_block<kPredOutThreads>(mask_words, ffn / 64, idx, count, clds);
-        }
+// ---------------------------------------------------------------------------------------
+// Block-wide exclusive prefix of the popcounts of mask words: pre[w] = set bits in words
+// [0, w) for w in [0, nwords]; the words are kept in LDS beside it.  Returns pre[nwords].
+// Thread t scans the contiguous words [t*per, (t+1)*per); wave scan + LDS across waves.
+template <int NT>
+__device__ __forceinline__ uint32_t mask_prefix(const uint64_t *__restrict__ mask_words, int nwords,
+                                                uint64_t *words_lds, uint32_t *pre_lds,
+                                                uint32_t *wave_tot /* [NT / 64] */)
+{
+    constexpr int NW = NT / kWave;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per = (nwords + NT - 1) / NT;
+    const int w0 = tid * per, w1 = min(nwords, w0 + per);
+    uint32_t mine = 0;
+    for (int w = w0; w < w1; ++w) {
+        const uint64_t word = mask_words[w];
+        words_lds[w] = word;
+        mine += (uint32_t)__popcll(word);
     }
+    uint32_t inc = mine;  // inclusive scan inside the wave
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_up((int)inc, o, 64);
+        if (lane >= o) inc += up;
+    }
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int k = 0; k < NW; ++k) {
+        const uint32_t v = wave_tot[k];
+        if (k < wave) before += v;
+        total += v;
+    }
+    uint32_t run = before + inc - mine;
+    for (int w = w0; w < w1; ++w) {
+        pre_lds[w] = run;
+        run += (uint32_t)__popcll(words_lds[w]);
+    }
+    if (tid == NT - 1) pre_lds[nwords] = total;
+    __syncthreads();
+    return total;
+}
+
+// Position of the j-th set bit (j < total) given the prefix above; all 64 lanes of a wave
+// call it with the same j and get the same answer.  Two ballots find the word (coarse
+// stride, then within the stride; nwords <= 4096), a third the bit inside the word.
+__device__ __forceinline__ int select_set_bit(const uint64_t *words_lds, const uint32_t *pre_lds,
+                                              int nwords, uint32_t j, int lane)
+{
+    const int step = (nwords + 63) >> 6;
+    const int wc = min(lane * step, nwords);
+    const int coarse = __popcll(__ballot(lane * step < nwords && pre_lds[wc] <= j)) - 1;
+    const int wf = coarse * step + lane;
+    const bool ok = lane < step && wf < nwords && pre_lds[min(wf, nwords)] <= j;
+    const int w = coarse * step + __popcll(__ballot(ok)) - 1;
+    const uint64_t word = words_lds[w];
+    const uint32_t rank = j - pre_lds[w];
+    const uint64_t below = word & ((1ull << lane) - 1ull);
+    const uint64_t hit = __ballot(((word >> lane) & 1ull) && (uint32_t)__popcll(below) == rank);
+    return w * 64 + (int)__builtin_ctzll(hit);
+}
+
+// ---------------------------------------------------------------------------------------
+// Stand-alone compaction of mask words into an ascending index list, by one workgroup.
+// Per pass of NT words: popcount prefix as above, then one wave per word; lane l owns
+// bit l and its rank inside the word is the popcount of the lower bits (what a ballot +
+// mbcnt pair gives for a live predicate).
+constexpr int kCompactThreads = 1024;
+
+__global__ __launch_bounds__(kCompactThreads) void k_compact(const uint64_t *__restrict__ mask_words,
+                                                             int nwords, int32_t *__restrict__ idx,
+                                                             int32_t *__restrict__ count)
+{
+    constexpr int NT = kCompactThreads, NW = NT / kWave;
+    __shared__ uint64_t words_lds[NT];
+    __shared__ uint32_t pre_lds[NT + 1];
+    __shared__ uint32_t wave_tot[NW];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t carry = 0;
+    for (int w0 = 0; w0 < nwords; w0 += NT) {
+        const int nhere = min(NT, nwords - w0);
+        const uint32_t total = mask_prefix<NT>(mask_words + w0, nhere, words_lds, pre_lds, wave_tot);
+        for (int q = wave; q < nhere; q += NW) {
+            const uint64_t wq = words_lds[q];
+            const uint64_t below = wq & ((1ull << lane) - 1ull);
+            if ((wq >> lane) & 1ull)
+                idx[carry + pre_lds[q] + (uint32_t)__popcll(below)] = (w0 + q) * 64 + lane;
+        }
+        carry += total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *count = (int32_t)carry;
 }
 
 }  // namespace pf

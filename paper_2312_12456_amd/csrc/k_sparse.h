@@ -1,46 +1,77 @@
-// Neuron-aware sparse FFN over a compacted index list (PowerInfer Sec. 5.4; the FFN block
+// Neuron-aware sparse FFN over the active neurons (PowerInfer Sec. 5.4; the FFN block
 // itself is Sec. 2.1, Fig. "bg-mlp"): only the FC1 / gate rows and FC2 columns of the listed
 // neurons are read.  All three matrices are neuron-major [ffn][d] fp16, so one neuron is one
 // contiguous run of 2d bytes (a multiple of 128 B at every model width used).
 //   k_up   : h[b][j] = act(row idx[j] . x[b] + bias)           one wave per listed neuron
-//   k_down : y[b][:] = b_down + sum_j h[b][j] * FC2^T[idx[j]]  d-tiles x neuron-chunks, then a
-//            deterministic combine of the chunk partials by the last workgroup of each tile
-// The number of listed neurons is read from device memory; grids are fixed.
+//   k_down : y[b][:] = b_down + sum_j h[b][j] * FC2^T[idx[j]]  one workgroup per 16 columns
+// The number of listed neurons is read from device memory; grids are fixed.  No kernel
+// uses device-scope fences or atomics: every sum has one owner and a fixed order.
 #pragma once
 #include "dev_util.h"
+#include "k_predict.h"
 
 namespace pf {
 
 constexpr int kUpThreads = 256;
 constexpr int kUpWaves = kUpThreads / kWave;
 
+// LDS bytes the up kernel needs beyond the staged activations when it compacts itself.
+inline size_t up_mask_lds_bytes(int ffn)
+{
+    const size_t nwords = (size_t)ffn / 64;
+    return nwords * sizeof(uint64_t) + (nwords + 1) * sizeof(uint32_t) + 64;
+}
+
 // ---------------------------------------------------------------------------------------
 // grid = any; waves stride over the list.  x is staged once per workgroup in LDS while the
 // first row of every wave is already in flight.
-template <int B, int ACT>
-__global__ __launch_bounds__(kUpThreads) void k_up(const __half *__restrict__ w_up,
-                                                   const __half *__restrict__ w_gate,
-                                                   const float *__restrict__ b_up,
-                                                   const float *__restrict__ x,
-                                                   const int32_t *__restrict__ idx,
-                                                   const int32_t *__restrict__ count_p,
-                                                   float *__restrict__ h, int d, int ffn)
+// FROM_MASK: the list is not given; every workgroup derives it from the predictor's mask
+// words (popcount prefix in LDS, then each wave selects its j-th set bit), writes the
+// entries it owns to idx_out and block 0 writes the count -- the compaction fused into its
+// consumer, so the layer step needs no separate compaction launch.
+template <int B, int ACT, bool FROM_MASK>
+__global__ __launch_bounds__(kUpThreads) void k_up(
+    const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
+    const float *__restrict__ b_up, const float *__restrict__ x,
+    const int32_t *__restrict__ idx_in, const int32_t *__restrict__ count_in,
+    const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
+    int32_t *__restrict__ count_out, float *__restrict__ h, int d, int ffn)
 {
     extern __shared__ float xs[];
+    __shared__ uint32_t wave_tot[kUpWaves];
     constexpr int U = 8;
     constexpr bool GATED = (ACT == 1);
-    const int n = min(max(*count_p, 0), ffn);
-    if ((int)blockIdx.x * kUpWaves >= n) return;  // uniform over the block
     const int lane = threadIdx.x & 63;
     const int wave = wave_uniform(threadIdx.x >> 6);
     const int nch = (d + kChunk - 1) / kChunk, kpad = nch * kChunk;
     const int stride = gridDim.x * kUpWaves;
+    const int nwords = ffn / 64;
+    uint64_t *words_lds = reinterpret_cast<uint64_t *>(xs + (size_t)B * kpad);
+    uint32_t *pre_lds = reinterpret_cast<uint32_t *>(words_lds + nwords);
+
+    int n;
+    if (FROM_MASK) {
+        n = (int)mask_prefix<kUpThreads>(mask_words, nwords, words_lds, pre_lds, wave_tot);
+        if (blockIdx.x == 0 && threadIdx.x == 0) *count_out = n;
+    } else {
+        n = min(max(*count_in, 0), ffn);
+    }
+    if ((int)blockIdx.x * kUpWaves >= n) return;  // uniform over the block
+
+    auto neuron_of = [&](int j) -> int {
+        if (FROM_MASK) {
+            const int i = select_set_bit(words_lds, pre_lds, nwords, (uint32_t)j, lane);
+            if (lane == 0) idx_out[j] = i;
+            return i;
+        }
+        return idx_in[j];
+    };
 
     int j = blockIdx.x * kUpWaves + wave;
     int i = 0;
     bool valid = false;
     if (j < n) {
-        i = idx[j];
+        i = neuron_of(j);
         valid = (unsigned)i < (unsigned)ffn;
         if (!valid) i = 0;
     }
@@ -67,7 +98,7 @@ __global__ __launch_bounds__(kUpThreads) void k_up(const __half *__restrict__ w_
         const bool vcur = valid;
         j += stride;
         if (j < n) {  // next row in flight before this row's reductions
-            i = idx[j];
+            i = neuron_of(j);
             valid = (unsigned)i < (unsigned)ffn;
             if (!valid) i = 0;
             load_group<U>(gu, w_up + (size_t)i * d, valid ? d : 0, 0, lane);
@@ -90,35 +121,36 @@ __global__ __launch_bounds__(kUpThreads) void k_up(const __half *__restrict__ w_
 }
 
 // ---------------------------------------------------------------------------------------
-constexpr int kDownThreads = 256;
+// FC2 over the listed neurons.  A workgroup owns kDownCols = 16 output columns and walks
+// the WHOLE list, so no partial sums ever leave the workgroup.  Lane l of a wave reads 16
+// bytes (8 columns): lanes 0..31 the first half of the 32-byte run of 32 different rows,
+// lanes 32..63 the second half of the same rows; a workgroup of 8 waves covers 256 rows per
+// load and keeps U loads per lane in flight.  The four 32-byte sectors of a 128-byte line
+// belong to four workgroups with consecutive tile numbers; tiles are numbered so that
+// consecutive tiles run on the same XCD (workgroups are dealt round-robin to the 8 XCDs),
+// hence every line is fetched from HBM once, into one L2.
+constexpr int kDownThreads = 512;
 constexpr int kDownWaves = kDownThreads / kWave;
-constexpr int kDownTile = 512;  // columns per workgroup: 8 per lane, one 16-byte load per row
+constexpr int kDownCols = 16;
+constexpr int kDownRowsPerLoad = kDownThreads / 2;  // rows one load instruction of the block covers
 
-// grid = (ceil(d / 512), max_chunks).  The listed neurons are cut into `eff` equal chunks
-// (eff derived from the device-side count, at least min_rows neurons each); block (tx, c)
-// sums chunk c over column tile tx.  Within a block wave w takes rows w, w+4, ... of the
-// chunk, U at a time; waves are combined in LDS in wave order, the block's partial goes
-// to `partial[c][b][d]`, and the last block to arrive on a tile (device-scope counter) adds
-// the partials in chunk order plus b_down into y.  The order of every sum is fixed.
 template <int B>
 __global__ __launch_bounds__(kDownThreads) void k_down(
     const __half *__restrict__ w_down, const float *__restrict__ b_down,
     const float *__restrict__ h, const int32_t *__restrict__ idx,
-    const int32_t *__restrict__ count_p, float *__restrict__ partial,
-    unsigned int *__restrict__ tile_arrive, float *__restrict__ y, int d, int ffn, int min_rows)
+    const int32_t *__restrict__ count_p, float *__restrict__ y, int d, int ffn, int ntiles)
 {
-    constexpr int U = 8;
-    __shared__ float red[kDownWaves - 1][B][kDownTile];
-    __shared__ int is_last;
+    constexpr int U = (B <= 2) ? 8 : 4;
+    __shared__ float red[kDownWaves][B][kDownCols];
     const int n = min(max(*count_p, 0), ffn);
-    const int eff = min(max((n + min_rows - 1) / min_rows, 1), (int)gridDim.y);
-    const int chunk = blockIdx.y;
-    if (chunk >= eff) return;  // uniform over the block
-    const int rows_per = (n + eff - 1) / eff;
-    const int j0 = chunk * rows_per, j1 = min(n, j0 + rows_per);
-    const int lane = threadIdx.x & 63;
-    const int wave = wave_uniform(threadIdx.x >> 6);
-    const int col = blockIdx.x * kDownTile + lane * 8;
+    // tile <-> block: blocks b, b+8, b+16, ... (same XCD) take consecutive tiles
+    const int per_xcd = (ntiles + 7) >> 3;
+    const int tile = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (tile >= ntiles) return;  // uniform over the block
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = lane >> 5;                 // which 16 bytes of the 32-byte run
+    const int rlane = wave * 32 + (lane & 31);  // row slot of this lane inside a load
+    const int col = tile * kDownCols + half * 8;
     const bool colok = col < d;
 
     float acc[B][8];
@@ -127,14 +159,14 @@ __global__ __launch_bounds__(kDownThreads) void k_down(
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
 
-    for (int j = j0 + wave; j < j1; j += kDownWaves * U) {
+    for (int j0 = 0; j0 < n; j0 += kDownRowsPerLoad * U) {
         uint4 w[U];
         float hv[U][B];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int jj = j + u * kDownWaves;
-            bool ok = jj < j1;
-            int i = ok ? idx[jj] : 0;
+            const int jj = j0 + u * kDownRowsPerLoad + rlane;
+            bool ok = jj < n;
+            const int i = ok ? idx[jj] : 0;
             ok = ok && (unsigned)i < (unsigned)ffn;
             if (ok && colok)
                 w[u] = ld16_stream(w_down + (size_t)i * d + col);
@@ -162,59 +194,29 @@ __global__ __launch_bounds__(kDownThreads) void k_down(
         }
     }
 
-    // combine the waves of this block in wave order
-    if (wave > 0) {
+    // sum over the 32 row slots of each half-wave: 16 lanes by DPP, then the two rows of 16
 #pragma unroll
-        for (int b = 0; b < B; ++b) {
-            *reinterpret_cast<float4 *>(&red[wave - 1][b][lane * 8]) =
-                make_float4(acc[b][0], acc[b][1], acc[b][2], acc[b][3]);
-            *reinterpret_cast<float4 *>(&red[wave - 1][b][lane * 8 + 4]) =
-                make_float4(acc[b][4], acc[b][5], acc[b][6], acc[b][7]);
+    for (int b = 0; b < B; ++b) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = acc[b][e];
+            v += dpp_f32<0xB1>(v);
+            v += dpp_f32<0x4E>(v);
+            v += dpp_f32<0x141>(v);
+            v += dpp_f32<0x140>(v);
+            v += __shfl_xor(v, 16, 64);
+            if ((lane & 31) == 0) red[wave][b][half * 8 + e] = v;
         }
     }
     __syncthreads();
-    if (wave == 0 && colok) {
+    if (threadIdx.x < B * kDownCols) {
+        const int b = threadIdx.x / kDownCols, c = threadIdx.x % kDownCols;
+        const int oc = tile * kDownCols + c;
+        if (oc < d) {
+            float s = b_down ? b_down[oc] : 0.f;
 #pragma unroll
-        for (int b = 0; b < B; ++b) {
-#pragma unroll
-            for (int wv = 0; wv < kDownWaves - 1; ++wv) {
-                const float4 a = *reinterpret_cast<const float4 *>(&red[wv][b][lane * 8]);
-                const float4 c = *reinterpret_cast<const float4 *>(&red[wv][b][lane * 8 + 4]);
-                acc[b][0] += a.x; acc[b][1] += a.y; acc[b][2] += a.z; acc[b][3] += a.w;
-                acc[b][4] += c.x; acc[b][5] += c.y; acc[b][6] += c.z; acc[b][7] += c.w;
-            }
-            float *dst = partial + ((size_t)chunk * B + b) * d + col;
-            *reinterpret_cast<float4 *>(dst) = make_float4(acc[b][0], acc[b][1], acc[b][2], acc[b][3]);
-            *reinterpret_cast<float4 *>(dst + 4) =
-                make_float4(acc[b][4], acc[b][5], acc[b][6], acc[b][7]);
-        }
-    }
-
-    // arrival on this column tile; the last block combines the chunk partials
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned int prev = atomicAdd(&tile_arrive[blockIdx.x], 1u);
-        is_last = (prev == (unsigned int)eff - 1u);
-        if (is_last) tile_arrive[blockIdx.x] = 0u;  // ready for the next launch
-    }
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();
-    const int c0 = blockIdx.x * kDownTile + threadIdx.x * 2;
-    if (c0 < d) {
-        const float2 bias = b_down ? *reinterpret_cast<const float2 *>(b_down + c0)
-                                   : make_float2(0.f, 0.f);
-#pragma unroll
-        for (int b = 0; b < B; ++b) {
-            float2 s = bias;
-            for (int c = 0; c < eff; ++c) {
-                const float2 p = *reinterpret_cast<const float2 *>(
-                    partial + ((size_t)c * B + b) * d + c0);
-                s.x += p.x;
-                s.y += p.y;
-            }
-            *reinterpret_cast<float2 *>(y + (size_t)b * d + c0) = s;
+            for (int wv = 0; wv < kDownWaves; ++wv) s += red[wv][b][c];
+            y[(size_t)b * d + oc] = s;
         }
     }
 }

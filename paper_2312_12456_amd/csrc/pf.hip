@@ -10,6 +10,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "k_predict.h"
 #include "k_sparse.h"
@@ -17,9 +18,14 @@
 namespace {
 
 constexpr int kMaxBatch = 8;
-constexpr int kChunksCap = 128;         // upper bound of neuron chunks in the FC2 kernel
+constexpr int kMaxFfn = 4096 * 64;      // the in-kernel bit select handles 4096 mask words
+constexpr int kProfPairsCap = 32768;    // event pairs one profiling pass may record
 constexpr int kLdsMax = 160 * 1024;     // LDS per workgroup on gfx950
 constexpr int kLdsDefault = 64 * 1024;  // what a kernel may use without opting in
+
+enum KernelId { K_PRED_HIDDEN = 0, K_PRED_OUT, K_COMPACT, K_UP, K_DOWN, K_GLUE, K_NUM };
+const char *const kKernelNames[K_NUM] = {"k_pred_hidden", "k_pred_out", "k_compact",
+                                         "k_up", "k_down", "k_glue"};
 
 }  // namespace
 
@@ -27,20 +33,22 @@ struct pf_ctx {
     int device = 0;
     int max_d = 0, max_ffn = 0, max_r = 0, max_batch = 0;
     int num_cu = 256;
-    int down_chunks = 64;    // grid.y of the FC2 kernel
-    int down_min_rows = 16;  // least neurons per chunk
     int up_grid_cap = 2048;
     int lds_budget = kLdsDefault;  // dynamic LDS a kernel of this context may request
     // scratch (device)
-    float *t = nullptr;             // [max_batch][max_r] predictor hidden vector
-    uint64_t *mask_words = nullptr; // [max_ffn / 64]
-    int32_t *idx = nullptr;         // [max_ffn]
-    int32_t *count = nullptr;       // [1]
-    float *h = nullptr;             // [max_batch][max_ffn] FC1 outputs of the listed neurons
-    float *partial = nullptr;       // [kChunksCap][max_batch][max_d]
-    unsigned int *arrive = nullptr; // [tiles + 1] arrival counters (zero between launches)
-    float *ybuf = nullptr;          // [max_batch][max_d] FFN output inside pf_stack_step
+    float *t = nullptr;              // [max_batch][max_r] predictor hidden vector
+    uint64_t *mask_words = nullptr;  // [max_ffn / 64]
+    int32_t *idx = nullptr;          // [max_ffn]
+    int32_t *count = nullptr;        // [1]
+    float *h = nullptr;              // [max_batch][max_ffn] FC1 outputs of the listed neurons
+    float *ybuf = nullptr;           // [max_batch][max_d] FFN output inside pf_stack_step
+    float *xbuf[2] = {nullptr, nullptr};  // [max_batch][max_d] layer inputs inside pf_stack_step
     hipStream_t capture_stream = nullptr;
+    // per-kernel timing with HIP events (pf_profile_begin / pf_profile_end)
+    bool prof_on = false;
+    bool capturing = false;
+    std::vector<hipEvent_t> prof_events;  // start/stop pairs, created on demand, reused
+    std::vector<int> prof_kernel;         // kernel id of each recorded pair
     char err[512] = {0};
 };
 
@@ -81,11 +89,12 @@ pf_status fail(pf_ctx *ctx, pf_status s, const char *fmt, ...)
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 inline int kpad_of(int k) { return cdiv(k, pf::kChunk) * pf::kChunk; }
 
-// Largest batch tile whose staged activations ([tile][kpad] fp32) fit the LDS budget.
-inline int batch_tile(const pf_ctx *ctx, int k, int B)
+// Largest batch tile whose staged activations ([tile][kpad] fp32) plus `extra` bytes fit LDS.
+inline int batch_tile(const pf_ctx *ctx, int k, int B, size_t extra)
 {
-    int fit = ctx->lds_budget / (kpad_of(k) * 4);
+    int fit = (int)(((size_t)ctx->lds_budget - extra) / ((size_t)kpad_of(k) * 4));
     if (fit > kMaxBatch) fit = kMaxBatch;
+    if (fit < 1) fit = 1;
     return fit < B ? fit : B;
 }
 
@@ -112,9 +121,12 @@ hipError_t allow_lds(K kernel)
 template <int B>
 hipError_t allow_lds_for_batch()
 {
-    hipError_t e = allow_lds(pf::k_pred_hidden<B>);
-    if (e == hipSuccess) e = allow_lds(pf::k_up<B, 0>);
-    if (e == hipSuccess) e = allow_lds(pf::k_up<B, 1>);
+    hipError_t e = allow_lds(pf::k_pred_hidden<B, false>);
+    if (e == hipSuccess) e = allow_lds(pf::k_pred_hidden<B, true>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up<B, 0, false>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up<B, 1, false>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up<B, 0, true>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up<B, 1, true>);
     return e;
 }
 
@@ -141,72 +153,116 @@ pf_status check_batch(pf_ctx *ctx, const pf_layer *layer, const void *x, int B)
     return PF_OK;
 }
 
+// Brackets one kernel launch with a pair of events on its stream while profiling is on.
+struct ProfScope {
+    pf_ctx *ctx;
+    hipStream_t st;
+    hipEvent_t stop = nullptr;
+    ProfScope(pf_ctx *c, int kernel, hipStream_t s) : ctx(c), st(s)
+    {
+        if (!c->prof_on || c->capturing || (int)c->prof_kernel.size() >= kProfPairsCap) return;
+        const size_t pair = c->prof_kernel.size();
+        while (c->prof_events.size() < 2 * (pair + 1)) {
+            hipEvent_t e = nullptr;
+            if (hipEventCreate(&e) != hipSuccess) return;
+            c->prof_events.push_back(e);
+        }
+        if (hipEventRecord(c->prof_events[2 * pair], s) != hipSuccess) return;
+        c->prof_kernel.push_back(kernel);
+        stop = c->prof_events[2 * pair + 1];
+    }
+    ~ProfScope()
+    {
+        if (stop) (void)hipEventRecord(stop, st);
+    }
+};
+
 // ---- launches ------------------------------------------------------------------------
-pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, int B, float *scores,
-                         uint64_t *mask_words, bool fuse_compact, hipStream_t st)
+// Predictor: hidden layer then output layer + ballot.  With glue_y the layer input is
+// formed inside the hidden kernel as norm(x + glue_y) and also written to x_new.
+pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
+                         float *x_new, int B, float *scores, uint64_t *mask_words, hipStream_t st)
 {
     const pf_layer_desc &D = L->desc;
     if (!L->w.p1 || !L->w.p2) return fail(ctx, PF_EINVAL, "layer has no predictor weights");
     const __half *p1 = static_cast<const __half *>(L->w.p1);
     const __half *p2 = static_cast<const __half *>(L->w.p2);
     // hidden layer, in batch tiles that fit LDS
-    const int tile = batch_tile(ctx, D.d, B);
+    const int tile = batch_tile(ctx, D.d, B, 1024);
     for (int b0 = 0; b0 < B; b0 += tile) {
         const int bt = (B - b0) < tile ? (B - b0) : tile;
         const size_t lds = (size_t)bt * kpad_of(D.d) * sizeof(float);
-        const dim3 grid(cdiv(D.r, pf::kPredThreads / pf::kWave));
-        PF_SWITCH_B(bt, hipLaunchKernelGGL(pf::k_pred_hidden<BT>, grid, dim3(pf::kPredThreads),
-                                           lds, st, p1, x + (size_t)b0 * D.d,
-                                           ctx->t + (size_t)b0 * D.r, D.d, D.r));
+        const dim3 grid(cdiv(D.r, pf::kPredWaves));
+        const size_t xo = (size_t)b0 * D.d;
+        ProfScope ps(ctx, K_PRED_HIDDEN, st);
+        if (glue_y) {
+            PF_SWITCH_B(bt, hipLaunchKernelGGL((pf::k_pred_hidden<BT, true>), grid,
+                                               dim3(pf::kPredThreads), lds, st, p1, x + xo,
+                                               glue_y + xo, x_new + xo, ctx->t + (size_t)b0 * D.r,
+                                               D.d, D.r));
+        } else {
+            PF_SWITCH_B(bt, hipLaunchKernelGGL((pf::k_pred_hidden<BT, false>), grid,
+                                               dim3(pf::kPredThreads), lds, st, p1, x + xo,
+                                               (const float *)nullptr, (float *)nullptr,
+                                               ctx->t + (size_t)b0 * D.r, D.d, D.r));
+        }
     }
     // output layer over the whole batch (its staged vector is only B * r floats)
     const size_t lds = (size_t)B * kpad_of(D.r) * sizeof(float);
     const dim3 grid(D.ffn / 64);
-    unsigned int *arrive = ctx->arrive;  // slot 0: predictor arrival counter
-    if (fuse_compact) {
-        PF_SWITCH_B(B, hipLaunchKernelGGL((pf::k_pred_out<BT, true>), grid,
-                                          dim3(pf::kPredOutThreads), lds, st, p2, L->w.p_bias,
-                                          ctx->t, D.r, D.ffn, L->thr_logit, scores, mask_words,
-                                          arrive, ctx->idx, ctx->count));
-    } else {
-        PF_SWITCH_B(B, hipLaunchKernelGGL((pf::k_pred_out<BT, false>), grid,
-                                          dim3(pf::kPredOutThreads), lds, st, p2, L->w.p_bias,
-                                          ctx->t, D.r, D.ffn, L->thr_logit, scores, mask_words,
-                                          arrive, (int32_t *)nullptr, (int32_t *)nullptr));
+    {
+        ProfScope ps(ctx, K_PRED_OUT, st);
+        PF_SWITCH_B(B, hipLaunchKernelGGL(pf::k_pred_out<BT>, grid, dim3(pf::kPredOutThreads), lds,
+                                          st, p2, L->w.p_bias, ctx->t, D.r, D.ffn, L->thr_logit,
+                                          scores, mask_words));
     }
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
 }
 
+// Sparse FFN.  Either an index list is given (idx_in, count_in) or mask words, from which
+// the FC1 kernel derives the list itself and leaves it in ctx->idx / ctx->count.
 pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
-                        const int32_t *idx, const int32_t *count, float *y, hipStream_t st)
+                        const int32_t *idx_in, const int32_t *count_in,
+                        const uint64_t *mask_words, float *y, hipStream_t st)
 {
     const pf_layer_desc &D = L->desc;
     const __half *w_up = static_cast<const __half *>(L->w.w_up);
     const __half *w_gate = static_cast<const __half *>(L->w.w_gate);
     const __half *w_down = static_cast<const __half *>(L->w.w_down);
-    const int tile = batch_tile(ctx, D.d, B);
+    const bool from_mask = mask_words != nullptr;
+    const size_t extra = from_mask ? pf::up_mask_lds_bytes(D.ffn) : 0;
+    const int tile = batch_tile(ctx, D.d, B, extra + 1024);
     int up_grid = cdiv(D.ffn, pf::kUpWaves);
     if (up_grid > ctx->up_grid_cap) up_grid = ctx->up_grid_cap;
+    const bool gated = D.act == PF_ACT_REGLU;
     for (int b0 = 0; b0 < B; b0 += tile) {
         const int bt = (B - b0) < tile ? (B - b0) : tile;
-        const size_t lds = (size_t)bt * kpad_of(D.d) * sizeof(float);
-        if (D.act == PF_ACT_REGLU) {
-            PF_SWITCH_B(bt, hipLaunchKernelGGL((pf::k_up<BT, 1>), dim3(up_grid),
-                                               dim3(pf::kUpThreads), lds, st, w_up, w_gate,
-                                               L->w.b_up, x + (size_t)b0 * D.d, idx, count,
-                                               ctx->h + (size_t)b0 * D.ffn, D.d, D.ffn));
-        } else {
-            PF_SWITCH_B(bt, hipLaunchKernelGGL((pf::k_up<BT, 0>), dim3(up_grid),
-                                               dim3(pf::kUpThreads), lds, st, w_up, w_gate,
-                                               L->w.b_up, x + (size_t)b0 * D.d, idx, count,
-                                               ctx->h + (size_t)b0 * D.ffn, D.d, D.ffn));
-        }
+        const size_t lds = (size_t)bt * kpad_of(D.d) * sizeof(float) + extra;
+        const float *xb = x + (size_t)b0 * D.d;
+        float *hb = ctx->h + (size_t)b0 * D.ffn;
+        ProfScope ps(ctx, K_UP, st);
+#define PF_UP(ACT, FM)                                                                            \
+    PF_SWITCH_B(bt, hipLaunchKernelGGL((pf::k_up<BT, ACT, FM>), dim3(up_grid),                    \
+                                       dim3(pf::kUpThreads), lds, st, w_up, w_gate, L->w.b_up, xb, \
+                                       idx_in, count_in, mask_words, ctx->idx, ctx->count, hb,    \
+                                       D.d, D.ffn))
+        if (gated && from_mask) { PF_UP(1, true); }
+        else if (gated) { PF_UP(1, false); }
+        else if (from_mask) { PF_UP(0, true); }
+        else { PF_UP(0, false); }
+#undef PF_UP
     }
-    const dim3 grid(cdiv(D.d, pf::kDownTile), ctx->down_chunks);
-    PF_SWITCH_B(B, hipLaunchKernelGGL(pf::k_down<BT>, grid, dim3(pf::kDownThreads), 0, st, w_down,
-                                      L->w.b_down, ctx->h, idx, count, ctx->partial,
-                                      ctx->arrive + 1, y, D.d, D.ffn, ctx->down_min_rows));
+    const int32_t *idx = from_mask ? ctx->idx : idx_in;
+    const int32_t *count = from_mask ? ctx->count : count_in;
+    const int ntiles = cdiv(D.d, pf::kDownCols);
+    const dim3 grid(cdiv(ntiles, 8) * 8);
+    {
+        ProfScope ps(ctx, K_DOWN, st);
+        PF_SWITCH_B(B, hipLaunchKernelGGL(pf::k_down<BT>, grid, dim3(pf::kDownThreads), 0, st,
+                                          w_down, L->w.b_down, ctx->h, idx, count, y, D.d, D.ffn,
+                                          ntiles));
+    }
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
 }
@@ -214,26 +270,36 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
 pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int d, int B, float *x_next,
                       hipStream_t st)
 {
-    hipLaunchKernelGGL(pf::k_glue, dim3(B), dim3(pf::kGlueThreads), 0, st, x, y, x_next, d);
+    {
+        ProfScope ps(ctx, K_GLUE, st);
+        hipLaunchKernelGGL(pf::k_glue, dim3(B), dim3(pf::kGlueThreads), 0, st, x, y, x_next, d);
+    }
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
 }
 
+// One decode step of the stack.  The glue between layer l-1 and layer l runs inside layer
+// l's hidden-layer kernel; only the glue after the last layer is a kernel of its own.
 pf_status stack_enqueue(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x, int B,
                         float *x_out, hipStream_t st)
 {
-    const float *cur = x;
+    const float *cur = x;  // input of the layer being enqueued (raw input of the previous one
+                           // until the hidden kernel has formed it)
     for (int l = 0; l < n_layers; ++l) {
         const pf_layer *L = layers[l];
-        pf_status s = launch_predict(ctx, L, cur, B, nullptr, ctx->mask_words, true, st);
+        pf_status s;
+        if (l == 0) {
+            s = launch_predict(ctx, L, cur, nullptr, nullptr, B, nullptr, ctx->mask_words, st);
+        } else {
+            float *xn = ctx->xbuf[l & 1];
+            s = launch_predict(ctx, L, cur, ctx->ybuf, xn, B, nullptr, ctx->mask_words, st);
+            cur = xn;
+        }
         if (s != PF_OK) return s;
-        s = launch_sparse(ctx, L, cur, B, ctx->idx, ctx->count, ctx->ybuf, st);
+        s = launch_sparse(ctx, L, cur, B, nullptr, nullptr, ctx->mask_words, ctx->ybuf, st);
         if (s != PF_OK) return s;
-        s = launch_glue(ctx, cur, ctx->ybuf, L->desc.d, B, x_out, st);
-        if (s != PF_OK) return s;
-        cur = x_out;
     }
-    return PF_OK;
+    return launch_glue(ctx, cur, ctx->ybuf, layers[0]->desc.d, B, x_out, st);
 }
 
 pf_status check_stack(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x, int B,
@@ -263,10 +329,12 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
     *out = nullptr;
     if (max_d < 1 || max_ffn < 1 || max_r < 1 || max_batch < 1 || max_batch > kMaxBatch || device < 0)
         return PF_EINVAL;
-    if (max_ffn % 64 != 0 || max_d % 8 != 0 || max_r % 8 != 0) return PF_ESHAPE;
-    // the staged hidden vector of the whole batch and one staged token must fit LDS
-    if ((size_t)max_batch * kpad_of(max_r) * sizeof(float) > (size_t)kLdsDefault - 16 * 1024 ||
-        (size_t)kpad_of(max_d) * sizeof(float) > (size_t)kLdsDefault)
+    if (max_ffn % 64 != 0 || max_d % 8 != 0 || max_r % 8 != 0 || max_ffn > kMaxFfn) return PF_ESHAPE;
+    // the staged hidden vector of the whole batch, and one staged token next to the mask
+    // words of the widest layer, must fit the LDS a kernel gets without opting in
+    if ((size_t)max_batch * kpad_of(max_r) * sizeof(float) > (size_t)kLdsDefault - 2048 ||
+        (size_t)kpad_of(max_d) * sizeof(float) + pf::up_mask_lds_bytes(max_ffn) + 1024 >
+            (size_t)kLdsMax)
         return PF_ESHAPE;
     pf_ctx *ctx = new (std::nothrow) pf_ctx();
     if (!ctx) return PF_ENOMEM;
@@ -283,30 +351,23 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         e = hipGetDeviceProperties(&prop, device);
         if (e != hipSuccess) { st = PF_EHIP; break; }
         if (prop.multiProcessorCount > 0) ctx->num_cu = prop.multiProcessorCount;
-        const int tiles = cdiv(max_d, pf::kDownTile);
-        int chunks = (4 * ctx->num_cu) / tiles;
-        if (chunks < 1) chunks = 1;
-        if (chunks > kChunksCap) chunks = kChunksCap;
-        ctx->down_chunks = chunks;
         ctx->up_grid_cap = 8 * ctx->num_cu;
-        if (const char *v = getenv("PF_DOWN_CHUNKS")) {
-            int c = atoi(v);
-            if (c >= 1 && c <= kChunksCap) ctx->down_chunks = c;
-        }
-        if (const char *v = getenv("PF_DOWN_MIN_ROWS")) {
-            int c = atoi(v);
-            if (c >= 1) ctx->down_min_rows = c;
-        }
         if (const char *v = getenv("PF_UP_GRID")) {
             int c = atoi(v);
             if (c >= 1 && c <= 65535) ctx->up_grid_cap = c;
         }
         // larger staged batches need the opt-in LDS size; without it batches are tiled smaller
-        if (prop.sharedMemPerBlock >= (size_t)kLdsMax || prop.maxSharedMemoryPerMultiProcessor >= (size_t)kLdsMax) {
+        if (prop.sharedMemPerBlock >= (size_t)kLdsMax ||
+            prop.maxSharedMemoryPerMultiProcessor >= (size_t)kLdsMax) {
             if (allow_lds_all() == hipSuccess)
                 ctx->lds_budget = kLdsMax;
             else
                 (void)hipGetLastError();
+        }
+        if ((size_t)kpad_of(max_d) * sizeof(float) + pf::up_mask_lds_bytes(max_ffn) + 1024 >
+            (size_t)ctx->lds_budget) {
+            st = PF_ESHAPE;
+            break;
         }
 #define PF_ALLOC(ptr, bytes)                                                  \
         e = hipMalloc(reinterpret_cast<void **>(&(ptr)), (bytes));            \
@@ -316,12 +377,11 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         PF_ALLOC(ctx->idx, (size_t)max_ffn * sizeof(int32_t));
         PF_ALLOC(ctx->count, 64);
         PF_ALLOC(ctx->h, (size_t)max_batch * max_ffn * sizeof(float));
-        PF_ALLOC(ctx->partial, (size_t)kChunksCap * max_batch * max_d * sizeof(float));
-        PF_ALLOC(ctx->arrive, (size_t)(tiles + 1) * sizeof(unsigned int));
         PF_ALLOC(ctx->ybuf, (size_t)max_batch * max_d * sizeof(float));
+        PF_ALLOC(ctx->xbuf[0], (size_t)max_batch * max_d * sizeof(float));
+        PF_ALLOC(ctx->xbuf[1], (size_t)max_batch * max_d * sizeof(float));
 #undef PF_ALLOC
-        e = hipMemset(ctx->arrive, 0, (size_t)(tiles + 1) * sizeof(unsigned int));
-        if (e == hipSuccess) e = hipMemset(ctx->count, 0, 64);
+        e = hipMemset(ctx->count, 0, 64);
         if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->capture_stream, hipStreamNonBlocking);
         if (e != hipSuccess) { st = PF_EHIP; break; }
     } while (0);
@@ -338,14 +398,15 @@ void pf_ctx_destroy(pf_ctx *ctx)
     if (!ctx) return;
     (void)hipSetDevice(ctx->device);
     if (ctx->capture_stream) (void)hipStreamDestroy(ctx->capture_stream);
+    for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
     (void)hipFree(ctx->t);
     (void)hipFree(ctx->mask_words);
     (void)hipFree(ctx->idx);
     (void)hipFree(ctx->count);
     (void)hipFree(ctx->h);
-    (void)hipFree(ctx->partial);
-    (void)hipFree(ctx->arrive);
     (void)hipFree(ctx->ybuf);
+    (void)hipFree(ctx->xbuf[0]);
+    (void)hipFree(ctx->xbuf[1]);
     delete ctx;
 }
 
@@ -400,7 +461,8 @@ pf_status pf_predict(pf_ctx *ctx, const pf_layer *layer, const float *x, int B, 
     pf_status s = check_batch(ctx, layer, x, B);
     if (s != PF_OK) return s;
     if (!mask_words) return fail(ctx, PF_EINVAL, "mask_words is null");
-    return launch_predict(ctx, layer, x, B, scores, mask_words, false, static_cast<hipStream_t>(stream));
+    return launch_predict(ctx, layer, x, nullptr, nullptr, B, scores, mask_words,
+                          static_cast<hipStream_t>(stream));
 }
 
 pf_status pf_compact(pf_ctx *ctx, const uint64_t *mask_words, int ffn, int32_t *idx, int32_t *count,
@@ -410,8 +472,11 @@ pf_status pf_compact(pf_ctx *ctx, const uint64_t *mask_words, int ffn, int32_t *
     if (!mask_words || !idx || !count) return fail(ctx, PF_EINVAL, "null argument");
     if (ffn < 0) return fail(ctx, PF_EINVAL, "negative ffn");
     if (ffn % 64 != 0) return fail(ctx, PF_ESHAPE, "ffn %d is not a multiple of 64", ffn);
-    hipLaunchKernelGGL(pf::k_compact, dim3(1), dim3(pf::kCompactThreads), 0,
-                       static_cast<hipStream_t>(stream), mask_words, ffn / 64, idx, count);
+    {
+        ProfScope ps(ctx, K_COMPACT, static_cast<hipStream_t>(stream));
+        hipLaunchKernelGGL(pf::k_compact, dim3(1), dim3(pf::kCompactThreads), 0,
+                           static_cast<hipStream_t>(stream), mask_words, ffn / 64, idx, count);
+    }
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
 }
@@ -422,7 +487,7 @@ pf_status pf_sparse_ffn(pf_ctx *ctx, const pf_layer *layer, const float *x, int 
     pf_status s = check_batch(ctx, layer, x, B);
     if (s != PF_OK) return s;
     if (!idx || !count || !y) return fail(ctx, PF_EINVAL, "null argument");
-    return launch_sparse(ctx, layer, x, B, idx, count, y, static_cast<hipStream_t>(stream));
+    return launch_sparse(ctx, layer, x, B, idx, count, nullptr, y, static_cast<hipStream_t>(stream));
 }
 
 pf_status pf_layer_step(pf_ctx *ctx, const pf_layer *layer, const float *x, int B, float *y,
@@ -432,9 +497,9 @@ pf_status pf_layer_step(pf_ctx *ctx, const pf_layer *layer, const float *x, int 
     if (s != PF_OK) return s;
     if (!y) return fail(ctx, PF_EINVAL, "y is null");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    s = launch_predict(ctx, layer, x, B, nullptr, ctx->mask_words, true, st);
+    s = launch_predict(ctx, layer, x, nullptr, nullptr, B, nullptr, ctx->mask_words, st);
     if (s != PF_OK) return s;
-    return launch_sparse(ctx, layer, x, B, ctx->idx, ctx->count, y, st);
+    return launch_sparse(ctx, layer, x, B, nullptr, nullptr, ctx->mask_words, y, st);
 }
 
 pf_status pf_ctx_last_active(pf_ctx *ctx, const uint64_t **mask_words, const int32_t **idx,
@@ -484,7 +549,9 @@ pf_status pf_plan_create(pf_ctx *ctx, pf_layer *const *layers, int n_layers, con
         delete plan;
         return fail(ctx, PF_EHIP, "hipStreamBeginCapture: %s", hipGetErrorString(e));
     }
+    ctx->capturing = true;
     s = stack_enqueue(ctx, layers, n_layers, x, B, x_out, cs);
+    ctx->capturing = false;
     e = hipStreamEndCapture(cs, &plan->graph);
     if (s == PF_OK && e != hipSuccess) s = fail(ctx, PF_EHIP, "hipStreamEndCapture: %s", hipGetErrorString(e));
     if (s == PF_OK) {
@@ -514,6 +581,38 @@ void pf_plan_destroy(pf_plan *plan)
     delete plan;
 }
 
+pf_status pf_profile_begin(pf_ctx *ctx)
+{
+    if (!ctx) return PF_EINVAL;
+    ctx->prof_kernel.clear();
+    ctx->prof_on = true;
+    return PF_OK;
+}
+
+pf_status pf_profile_end(pf_ctx *ctx, pf_kernel_stat *stats, int capacity, int *n_out)
+{
+    if (!ctx) return PF_EINVAL;
+    if (!stats || !n_out || capacity < K_NUM)
+        return fail(ctx, PF_EINVAL, "stats needs %d entries", (int)K_NUM);
+    ctx->prof_on = false;
+    for (int k = 0; k < K_NUM; ++k) {
+        stats[k].name = kKernelNames[k];
+        stats[k].launches = 0;
+        stats[k].total_ms = 0.0;
+    }
+    *n_out = K_NUM;
+    for (size_t p = 0; p < ctx->prof_kernel.size(); ++p) {
+        PF_HIP(ctx, hipEventSynchronize(ctx->prof_events[2 * p + 1]));
+        float ms = 0.f;
+        PF_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_events[2 * p], ctx->prof_events[2 * p + 1]));
+        pf_kernel_stat &st = stats[ctx->prof_kernel[p]];
+        st.launches += 1;
+        st.total_ms += (double)ms;
+    }
+    ctx->prof_kernel.clear();
+    return PF_OK;
+}
+
 const char *pf_strerror(pf_status s)
 {
     switch (s) {
@@ -529,6 +628,6 @@ const char *pf_strerror(pf_status s)
 
 const char *pf_last_error(const pf_ctx *ctx) { return ctx ? ctx->err : ""; }
 
-const char *pf_version(void) { return "libpf 0.1 (gfx950)"; }
+const char *pf_version(void) { return "libpf 0.2 (gfx950)"; }
 
 }  // extern "C"

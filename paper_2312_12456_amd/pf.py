@@ -20,7 +20,7 @@ EXPORTS = [
     "pf_ctx_create", "pf_ctx_destroy", "pf_layer_create", "pf_layer_destroy", "pf_predict",
     "pf_compact", "pf_sparse_ffn", "pf_layer_step", "pf_ctx_last_active", "pf_stack_glue",
     "pf_stack_step", "pf_plan_create", "pf_plan_run", "pf_plan_destroy", "pf_strerror",
-    "pf_last_error", "pf_version",
+    "pf_last_error", "pf_version", "pf_profile_begin", "pf_profile_end",
 ]
 
 
@@ -39,6 +39,11 @@ class LayerWeights(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in
                 ("w_up", "w_gate", "w_down", "s_up", "s_gate", "s_down", "b_up", "b_down", "p1",
                  "p2", "p_bias")]
+
+
+class KernelStat(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char_p), ("launches", ctypes.c_uint64),
+                ("total_ms", ctypes.c_double)]
 
 
 _lib = None
@@ -76,6 +81,8 @@ def lib():
         L.pf_last_error.argtypes = [P]
         L.pf_last_error.restype = ctypes.c_char_p
         L.pf_version.restype = ctypes.c_char_p
+        L.pf_profile_begin.argtypes = [P]
+        L.pf_profile_end.argtypes = [P, ctypes.POINTER(KernelStat), I, ctypes.POINTER(I)]
         _lib = L
     return _lib
 
@@ -160,6 +167,17 @@ class Context:
         B, d = x.shape
         self.check(lib().pf_stack_glue(self._h, _dev_ptr(x, torch.float32), _dev_ptr(y, torch.float32, B * d),
                                        d, B, _dev_ptr(x_next, torch.float32, B * d), _stream_ptr(stream)))
+
+    def profile_begin(self):
+        self.check(lib().pf_profile_begin(self._h))
+
+    def profile_end(self):
+        """-> {kernel name: (launches, total_ms)} measured with HIP events per launch."""
+        stats = (KernelStat * 16)()
+        n = ctypes.c_int(0)
+        self.check(lib().pf_profile_end(self._h, stats, 16, ctypes.byref(n)))
+        return {stats[k].name.decode(): (int(stats[k].launches), float(stats[k].total_ms))
+                for k in range(n.value)}
 
     def stack_step(self, layers, x, x_out, stream=None):
         B = x.shape[0]

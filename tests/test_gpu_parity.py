@@ -245,6 +245,15 @@ def test_stack_step_teacher_forced_and_plan_replay(pf, oracle):
     ctx.stack_step(Ls, x0, out_eager)
     torch.cuda.synchronize()
     assert torch.isfinite(out_eager).all()
+    # the stack fuses the glue into the next layer's predictor kernel: it must agree with the
+    # chain of stand-alone layer_step + stack_glue calls checked above (same sets, fp32 rounding)
+    xc = x0.clone()
+    yc = torch.empty_like(x0)
+    for l in range(cfg.layers):
+        ctx.layer_step(Ls[l], xc, yc)
+        ctx.stack_glue(xc, yc, xc)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out_eager.cpu().numpy(), xc.cpu().numpy(), atol=1e-4, rtol=0)
     out_plan = torch.zeros_like(x0)
     plan = pf.Plan(ctx, Ls, x0, out_plan)
     for _ in range(3):
