@@ -11,9 +11,10 @@ the timed region.  Prints ONE JSON line.
 Three legs:
   value         K tokens through the recorded HIP graph of the stack (timed with host clocks
                 between device synchronisations);
-  roofline      a second, eager pass in which the library brackets every kernel launch with
-                HIP events on its stream; the dominant kernel's algorithmic bytes per launch
-                over its mean duration against the 8 TB/s HBM peak;
+  roofline      a second, eager pass in which the library has every kernel launch stamp a
+                pair of HIP events with its start and end on its stream; the dominant
+                kernel's algorithmic bytes per launch over its mean duration against the
+                8 TB/s HBM peak;
   cpu_baseline  the CPU oracle timed on the host cores on a bounded sample of the same
                 workload (a few layers x a few tokens, scaled by the layer count).
 """

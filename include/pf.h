@@ -152,10 +152,12 @@ void pf_plan_destroy(pf_plan *plan);
 
 /* Per-kernel timing for measurement.  Between pf_profile_begin and pf_profile_end every
  * kernel the library launches eagerly on this context (not inside a recorded plan) is
- * bracketed by a pair of HIP events on its own stream, up to 32768 launches.
+ * timed with a pair of HIP events on its own stream, up to 32768 launches.
  * pf_profile_end waits for the recorded events (the only call here that synchronises with
  * the host) and fills one entry per kernel: name (host string), launches, summed ms.
- * stats: HOST array of `capacity` >= 6 entries; *n_out receives the number filled. */
+ * stats: HOST array of `capacity` >= 8 entries; *n_out receives the number filled.
+ * The events are stamped by the launch itself (hipExtLaunchKernelGGL) with the kernel's
+ * start and end on its stream, so launch gaps are not part of the figures. */
 typedef struct {
     const char *name;
     uint64_t launches;

@@ -134,15 +134,17 @@ constexpr int kDownWaves = kDownThreads / kWave;
 constexpr int kDownCols = 16;
 constexpr int kDownRowsPerLoad = kDownThreads / 2;  // rows one load instruction of the block covers
 
-template <int B>
+// SPEC: idx and h are the library's own scratch (capacity ffn), so the index and h loads
+// of the first pass are issued before the count has arrived and overlap with it.
+template <int B, bool SPEC>
 __global__ __launch_bounds__(kDownThreads) void k_down(
     const __half *__restrict__ w_down, const float *__restrict__ b_down,
     const float *__restrict__ h, const int32_t *__restrict__ idx,
     const int32_t *__restrict__ count_p, float *__restrict__ y, int d, int ffn, int ntiles)
 {
     constexpr int U = (B <= 2) ? 8 : 4;
+    constexpr int STEP = kDownRowsPerLoad * U;
     __shared__ float red[kDownWaves][B][kDownCols];
-    const int n = min(max(*count_p, 0), ffn);
     // tile <-> block: blocks b, b+8, b+16, ... (same XCD) take consecutive tiles
     const int per_xcd = (ntiles + 7) >> 3;
     const int tile = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
@@ -159,21 +161,42 @@ __global__ __launch_bounds__(kDownThreads) void k_down(
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
 
-    for (int j0 = 0; j0 < n; j0 += kDownRowsPerLoad * U) {
+    int n = 0;
+    bool have_n = false;
+    for (int j0 = 0; j0 == 0 || j0 < n; j0 += STEP) {
         uint4 w[U];
         float hv[U][B];
+        int iv[U];
+        if (SPEC) {  // loads that depend on the slot number only
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int jc = min(j0 + u * kDownRowsPerLoad + rlane, ffn - 1);
+                iv[u] = idx[jc];
+#pragma unroll
+                for (int b = 0; b < B; ++b) hv[u][b] = h[(size_t)b * ffn + jc];
+            }
+        }
+        if (!have_n) {
+            n = min(max(*count_p, 0), ffn);
+            have_n = true;
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int jj = j0 + u * kDownRowsPerLoad + rlane;
             bool ok = jj < n;
-            const int i = ok ? idx[jj] : 0;
-            ok = ok && (unsigned)i < (unsigned)ffn;
+            if (!SPEC) iv[u] = ok ? idx[jj] : 0;
+            ok = ok && (unsigned)iv[u] < (unsigned)ffn;
             if (ok && colok)
-                w[u] = ld16_stream(w_down + (size_t)i * d + col);
+                w[u] = ld16_stream(w_down + (size_t)iv[u] * d + col);
             else
                 w[u] = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-            for (int b = 0; b < B; ++b) hv[u][b] = ok ? h[(size_t)b * ffn + jj] : 0.f;
+            for (int b = 0; b < B; ++b) {
+                if (SPEC)
+                    hv[u][b] = ok ? hv[u][b] : 0.f;
+                else
+                    hv[u][b] = ok ? h[(size_t)b * ffn + jj] : 0.f;
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {

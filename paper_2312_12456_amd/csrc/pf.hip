@@ -2,6 +2,7 @@
 // declared in include/pf.h.  gfx950 only.
 #include "../../include/pf.h"
 
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -153,12 +154,12 @@ pf_status check_batch(pf_ctx *ctx, const pf_layer *layer, const void *x, int B)
     return PF_OK;
 }
 
-// Brackets one kernel launch with a pair of events on its stream while profiling is on.
+// While profiling is on, hands out a pair of events for one kernel launch; the launch then
+// goes through hipExtLaunchKernelGGL, which stamps them with the kernel's own start and
+// end times on its stream (nothing but the kernel lies between the two stamps).
 struct ProfScope {
-    pf_ctx *ctx;
-    hipStream_t st;
-    hipEvent_t stop = nullptr;
-    ProfScope(pf_ctx *c, int kernel, hipStream_t s) : ctx(c), st(s)
+    hipEvent_t start = nullptr, stop = nullptr;
+    ProfScope(pf_ctx *c, int kernel)
     {
         if (!c->prof_on || c->capturing || (int)c->prof_kernel.size() >= kProfPairsCap) return;
         const size_t pair = c->prof_kernel.size();
@@ -167,15 +168,20 @@ struct ProfScope {
             if (hipEventCreate(&e) != hipSuccess) return;
             c->prof_events.push_back(e);
         }
-        if (hipEventRecord(c->prof_events[2 * pair], s) != hipSuccess) return;
         c->prof_kernel.push_back(kernel);
+        start = c->prof_events[2 * pair];
         stop = c->prof_events[2 * pair + 1];
     }
-    ~ProfScope()
-    {
-        if (stop) (void)hipEventRecord(stop, st);
-    }
 };
+
+#define PF_LAUNCH(ps, kernel, grid, block, lds, st, ...)                                          \
+    do {                                                                                          \
+        if ((ps).start)                                                                           \
+            hipExtLaunchKernelGGL(kernel, grid, block, lds, st, (ps).start, (ps).stop, 0,         \
+                                  __VA_ARGS__);                                                   \
+        else                                                                                      \
+            hipLaunchKernelGGL(kernel, grid, block, lds, st, __VA_ARGS__);                        \
+    } while (0)
 
 // ---- launches ------------------------------------------------------------------------
 // Predictor: hidden layer then output layer + ballot.  With glue_y the layer input is
@@ -194,14 +200,14 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
         const size_t lds = (size_t)bt * kpad_of(D.d) * sizeof(float);
         const dim3 grid(cdiv(D.r, pf::kPredWaves));
         const size_t xo = (size_t)b0 * D.d;
-        ProfScope ps(ctx, K_PRED_HIDDEN, st);
+        ProfScope ps(ctx, K_PRED_HIDDEN);
         if (glue_y) {
-            PF_SWITCH_B(bt, hipLaunchKernelGGL((pf::k_pred_hidden<BT, true>), grid,
+            PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_pred_hidden<BT, true>), grid,
                                                dim3(pf::kPredThreads), lds, st, p1, x + xo,
                                                glue_y + xo, x_new + xo, ctx->t + (size_t)b0 * D.r,
                                                D.d, D.r));
         } else {
-            PF_SWITCH_B(bt, hipLaunchKernelGGL((pf::k_pred_hidden<BT, false>), grid,
+            PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_pred_hidden<BT, false>), grid,
                                                dim3(pf::kPredThreads), lds, st, p1, x + xo,
                                                (const float *)nullptr, (float *)nullptr,
                                                ctx->t + (size_t)b0 * D.r, D.d, D.r));
@@ -211,8 +217,8 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
     const size_t lds = (size_t)B * kpad_of(D.r) * sizeof(float);
     const dim3 grid(D.ffn / 64);
     {
-        ProfScope ps(ctx, K_PRED_OUT, st);
-        PF_SWITCH_B(B, hipLaunchKernelGGL(pf::k_pred_out<BT>, grid, dim3(pf::kPredOutThreads), lds,
+        ProfScope ps(ctx, K_PRED_OUT);
+        PF_SWITCH_B(B, PF_LAUNCH(ps, pf::k_pred_out<BT>, grid, dim3(pf::kPredOutThreads), lds,
                                           st, p2, L->w.p_bias, ctx->t, D.r, D.ffn, L->thr_logit,
                                           scores, mask_words));
     }
@@ -241,9 +247,9 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
         const size_t lds = (size_t)bt * kpad_of(D.d) * sizeof(float) + extra;
         const float *xb = x + (size_t)b0 * D.d;
         float *hb = ctx->h + (size_t)b0 * D.ffn;
-        ProfScope ps(ctx, K_UP, st);
+        ProfScope ps(ctx, K_UP);
 #define PF_UP(ACT, FM)                                                                            \
-    PF_SWITCH_B(bt, hipLaunchKernelGGL((pf::k_up<BT, ACT, FM>), dim3(up_grid),                    \
+    PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_up<BT, ACT, FM>), dim3(up_grid),                    \
                                        dim3(pf::kUpThreads), lds, st, w_up, w_gate, L->w.b_up, xb, \
                                        idx_in, count_in, mask_words, ctx->idx, ctx->count, hb,    \
                                        D.d, D.ffn))
@@ -258,10 +264,16 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     const int ntiles = cdiv(D.d, pf::kDownCols);
     const dim3 grid(cdiv(ntiles, 8) * 8);
     {
-        ProfScope ps(ctx, K_DOWN, st);
-        PF_SWITCH_B(B, hipLaunchKernelGGL(pf::k_down<BT>, grid, dim3(pf::kDownThreads), 0, st,
-                                          w_down, L->w.b_down, ctx->h, idx, count, y, D.d, D.ffn,
-                                          ntiles));
+        ProfScope ps(ctx, K_DOWN);
+        if (from_mask) {
+            PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_down<BT, true>), grid, dim3(pf::kDownThreads),
+                                              0, st, w_down, L->w.b_down, ctx->h, idx, count, y,
+                                              D.d, D.ffn, ntiles));
+        } else {
+            PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_down<BT, false>), grid,
+                                              dim3(pf::kDownThreads), 0, st, w_down, L->w.b_down,
+                                              ctx->h, idx, count, y, D.d, D.ffn, ntiles));
+        }
     }
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
@@ -271,8 +283,8 @@ pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int d, int B,
                       hipStream_t st)
 {
     {
-        ProfScope ps(ctx, K_GLUE, st);
-        hipLaunchKernelGGL(pf::k_glue, dim3(B), dim3(pf::kGlueThreads), 0, st, x, y, x_next, d);
+        ProfScope ps(ctx, K_GLUE);
+        PF_LAUNCH(ps, pf::k_glue, dim3(B), dim3(pf::kGlueThreads), 0, st, x, y, x_next, d);
     }
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
@@ -473,9 +485,9 @@ pf_status pf_compact(pf_ctx *ctx, const uint64_t *mask_words, int ffn, int32_t *
     if (ffn < 0) return fail(ctx, PF_EINVAL, "negative ffn");
     if (ffn % 64 != 0) return fail(ctx, PF_ESHAPE, "ffn %d is not a multiple of 64", ffn);
     {
-        ProfScope ps(ctx, K_COMPACT, static_cast<hipStream_t>(stream));
-        hipLaunchKernelGGL(pf::k_compact, dim3(1), dim3(pf::kCompactThreads), 0,
-                           static_cast<hipStream_t>(stream), mask_words, ffn / 64, idx, count);
+        ProfScope ps(ctx, K_COMPACT);
+        PF_LAUNCH(ps, pf::k_compact, dim3(1), dim3(pf::kCompactThreads), 0,
+                  static_cast<hipStream_t>(stream), mask_words, ffn / 64, idx, count);
     }
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
