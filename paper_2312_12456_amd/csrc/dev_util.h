@@ -10,6 +10,21 @@ namespace pf {
 constexpr int kWave = 64;      // CDNA wavefront width
 constexpr int kChunk = 512;    // elements of a row one wave covers per 16-byte load (64 lanes x 8 fp16)
 
+// Phase timestamps for kernel tuning, compiled in only with -DPF_TRACE: thread 0 of a block
+// stores the 100 MHz wall clock at a few program points into a host-provided buffer.
+#ifdef PF_TRACE
+__device__ unsigned long long *g_pf_trace = nullptr;  // [slot][4096 blocks][8 stamps]
+#define PF_TSTAMP(slot, k)                                                                   \
+    do {                                                                                     \
+        if (threadIdx.x == 0 && g_pf_trace && blockIdx.x < 4096)                             \
+            g_pf_trace[((size_t)(slot) * 4096 + blockIdx.x) * 8 + (k)] = wall_clock64();     \
+    } while (0)
+#else
+#define PF_TSTAMP(slot, k) \
+    do {                   \
+    } while (0)
+#endif
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v)
 {
@@ -32,15 +47,49 @@ __device__ __forceinline__ float wave_sum(float v)
     return (a + b) + (c + d);
 }
 
-// 16-byte streaming load (weights are read once per token: no reuse to keep in cache).
+// Buffer resources: every weight and activation load goes through a raw buffer descriptor
+// (base, byte size) held in scalar registers.  Lanes whose offset lies past the end get
+// zeros from the hardware, so loads need no branches -- which also lets the compiler count
+// outstanding loads exactly and start the FMAs on the first chunk while later ones are
+// still in flight.  Sizes are 32-bit: a matrix must stay below 4 GiB.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 ld16_stream(const void *p)
+constexpr uint32_t kOobOffset = 0xfffffff0u;  // an offset past any buffer: the load returns 0
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
 {
-    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
+// 16-byte streaming load (weights are read once per token: no reuse to keep in cache).
+__device__ __forceinline__ uint4 ld16_stream(rsrc_t r, uint32_t byte_off)
+{
+#ifndef PF_PLAIN_LOADS
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 2);  // nt
+#else
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+#endif
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// 16-byte load of fp32 activations (shared by many workgroups: keep it cacheable).
+__device__ __forceinline__ float4 ld16_f32(rsrc_t r, uint32_t byte_off)
+{
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+    // (element-wise __builtin_bit_cast on the vector's components is miscompiled into a
+    // splat of the first dword by this toolchain; __uint_as_float is not)
+    return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z),
+                       __uint_as_float(v.w));
+}
+
 __device__ __forceinline__ int wave_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Descriptor of row `i` (wave-uniform) of a neuron-major fp16 matrix with rows of K values;
+// an invalid row gets an empty buffer, i.e. reads as zeros.
+__device__ __forceinline__ rsrc_t row_rsrc(const __half *base, int i, int K, bool valid)
+{
+    return make_rsrc(base + (size_t)i * K, valid ? (uint32_t)K * 2u : 0u);
+}
 
 // A group of U 16-byte weight loads of one row, kept in registers.
 template <int U>
@@ -48,19 +97,13 @@ struct WGroup {
     uint4 w[U];
 };
 
-// Issue the loads of chunks it0 .. it0+U-1 of a row of K fp16 values (lanes past the end get zeros).
+// Issue the loads of chunks it0 .. it0+U-1 of a row (lanes and chunks past the end get zeros).
 template <int U>
-__device__ __forceinline__ void load_group(WGroup<U> &g, const __half *__restrict__ row, int K,
-                                           int it0, int lane)
+__device__ __forceinline__ void load_group(WGroup<U> &g, rsrc_t row, int it0, int lane)
 {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int c = (it0 + u) * kChunk + lane * 8;
-        if (c < K)
-            g.w[u] = ld16_stream(row + c);
-        else
-            g.w[u] = make_uint4(0u, 0u, 0u, 0u);
-    }
+    for (int u = 0; u < U; ++u)
+        g.w[u] = ld16_stream(row, (uint32_t)((it0 + u) * kChunk + lane * 8) * 2u);
 }
 
 __device__ __forceinline__ float h_lo(uint32_t p)
@@ -95,18 +138,68 @@ __device__ __forceinline__ int lds_slot(int e)
     return (e & ~511) + (((e & 7) >> 2) << 8) + (((e & 511) >> 3) << 2) + (e & 3);
 }
 
-// Cooperative copy of v[B][K] (global fp32) into the LDS layout above, zero padded to kpad.
-// K % 4 == 0.  All threads of the block call it; the caller synchronises afterwards.
-template <int B>
-__device__ __forceinline__ void stage_vector(float *__restrict__ xs, const float *__restrict__ v,
-                                             int K, int kpad)
+// Cooperative copy of v[B][K] (global fp32) into the LDS layout above, zero padded to kpad,
+// in two phases so that the caller can put other work between them: stage_issue puts the
+// global loads of the first pass in flight (S strides x B tokens per thread, kept in
+// registers), stage_commit writes them to LDS and, for vectors longer than one pass, copies
+// the rest.  Vector memory returns in issue order, so issuing these few loads BEFORE the
+// weight loads lets the workgroup pass its barrier as soon as the activations are in, and
+// the FMAs then consume weight chunks as they arrive.  K % 4 == 0.  All threads of the
+// block call both; the caller synchronises after stage_commit.  S = strides per pass.
+// The LDS image is followed by 4 floats of scrap: a thread whose stride lies past the vector
+// writes there, so the commit has no branch the compiler could sink the loads into.
+constexpr int kStageScrap = 4;
+
+template <int B, int S>
+struct Staged {
+    float4 val[S][B];
+};
+
+template <int B, int S>
+__device__ __forceinline__ void stage_issue(Staged<B, S> &st, const float *__restrict__ v, int K)
 {
-    for (int e = threadIdx.x * 4; e < kpad; e += blockDim.x * 4) {
+    const rsrc_t r = make_rsrc(v, (uint32_t)B * (uint32_t)K * 4u);
+    const int step = blockDim.x * 4;
 #pragma unroll
-        for (int b = 0; b < B; ++b) {
-            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (e < K) val = *reinterpret_cast<const float4 *>(v + (size_t)b * K + e);
-            *reinterpret_cast<float4 *>(xs + b * kpad + lds_slot(e)) = val;
+    for (int s = 0; s < S; ++s) {
+        const int e = threadIdx.x * 4 + s * step;
+#pragma unroll
+        for (int b = 0; b < B; ++b)
+            st.val[s][b] = ld16_f32(r, e < K ? (uint32_t)(b * K + e) * 4u : kOobOffset);
+    }
+}
+
+template <int B, int S>
+__device__ __forceinline__ void stage_commit(const Staged<B, S> &st, float *__restrict__ xs,
+                                             const float *__restrict__ v, int K, int kpad)
+{
+    const int step = blockDim.x * 4;
+    const int scrap = B * kpad;
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        const int e = threadIdx.x * 4 + s * step;
+#pragma unroll
+        for (int b = 0; b < B; ++b)
+            *reinterpret_cast<float4 *>(xs + (e < kpad ? b * kpad + lds_slot(e) : scrap)) =
+                st.val[s][b];
+    }
+    const rsrc_t r = make_rsrc(v, (uint32_t)B * (uint32_t)K * 4u);
+    for (int e0 = threadIdx.x * 4 + S * step; e0 < kpad; e0 += step * S) {  // longer vectors
+        float4 val[S][B];
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const int e = e0 + s * step;
+#pragma unroll
+            for (int b = 0; b < B; ++b)
+                val[s][b] = ld16_f32(r, e < K ? (uint32_t)(b * K + e) * 4u : kOobOffset);
+        }
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const int e = e0 + s * step;
+#pragma unroll
+            for (int b = 0; b < B; ++b)
+                *reinterpret_cast<float4 *>(xs + (e < kpad ? b * kpad + lds_slot(e) : scrap)) =
+                    val[s][b];
         }
     }
 }

@@ -31,32 +31,57 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
     extern __shared__ float xs[];
     __shared__ float ss_w[kPredWaves][B];
     constexpr int U = 8;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = wave_uniform(threadIdx.x >> 6);
     const int nch = (d + kChunk - 1) / kChunk, kpad = nch * kChunk;
     const int m = blockIdx.x * kPredWaves + wave;
     const bool live = m < r;
-    const __half *row = p1 + (size_t)(live ? m : 0) * d;
+    const rsrc_t row = row_rsrc(p1, live ? m : 0, d, live);
 
+    PF_TSTAMP(0, 0);
+    constexpr int SS = (B >= 4) ? 1 : 4 / B;
+    Staged<B, SS> st;
+    if (!GLUE) stage_issue<B, SS>(st, x, d);
     WGroup<U> g;
-    load_group<U>(g, row, live ? d : 0, 0, lane);  // in flight while x is staged
     float scale[B];
     if (GLUE) {
         float ss[B];
 #pragma unroll
         for (int b = 0; b < B; ++b) ss[b] = 0.f;
-        for (int e = threadIdx.x * 4; e < kpad; e += kPredThreads * 4) {
+        constexpr int S = (B >= 4) ? 1 : 4 / B;  // strides whose loads are issued together
+        constexpr int step = kPredThreads * 4;
+        bool issued = false;
+        const rsrc_t xr = make_rsrc(x, (uint32_t)B * (uint32_t)d * 4u);
+        const rsrc_t yr = make_rsrc(yp, (uint32_t)B * (uint32_t)d * 4u);
+        for (int e0 = threadIdx.x * 4; e0 < kpad; e0 += step * S) {
+            float4 va[S][B], vc[S][B];
 #pragma unroll
-            for (int b = 0; b < B; ++b) {
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (e < d) {
-                    const float4 a = *reinterpret_cast<const float4 *>(x + (size_t)b * d + e);
-                    const float4 c = *reinterpret_cast<const float4 *>(yp + (size_t)b * d + e);
-                    v = make_float4(a.x + c.x, a.y + c.y, a.z + c.z, a.w + c.w);
+            for (int s = 0; s < S; ++s) {
+                const int e = e0 + s * step;
+#pragma unroll
+                for (int b = 0; b < B; ++b) {
+                    const uint32_t off = e < d ? (uint32_t)(b * d + e) * 4u : kOobOffset;
+                    va[s][b] = ld16_f32(xr, off);
+                    vc[s][b] = ld16_f32(yr, off);
                 }
-                ss[b] = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss[b]))));
-                *reinterpret_cast<float4 *>(xs + b * kpad + lds_slot(e)) = v;
+            }
+            // the row's own loads queue up behind the first pass of activations
+            if (!issued) {
+                load_group<U>(g, row, 0, lane);
+                issued = true;
+            }
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const int e = e0 + s * step;
+#pragma unroll
+                for (int b = 0; b < B; ++b) {  // strides past the vector hold zeros: scrap slot
+                    const float4 a = va[s][b], c = vc[s][b];
+                    const float4 v = make_float4(a.x + c.x, a.y + c.y, a.z + c.z, a.w + c.w);
+                    ss[b] = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss[b]))));
+                    *reinterpret_cast<float4 *>(xs + (e < kpad ? b * kpad + lds_slot(e) : B * kpad)) = v;
+                }
             }
         }
+        if (!issued) load_group<U>(g, row, 0, lane);  // threads past a short vector
 #pragma unroll
         for (int b = 0; b < B; ++b) {
             const float s = wave_sum(ss[b]);
@@ -81,18 +106,20 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
             }
         }
     } else {
-        stage_vector<B>(xs, x, d, kpad);
+        load_group<U>(g, row, 0, lane);
+        stage_commit<B, SS>(st, xs, x, d, kpad);
         __syncthreads();
 #pragma unroll
         for (int b = 0; b < B; ++b) scale[b] = 1.f;
     }
 
+    PF_TSTAMP(0, 1);
     float acc[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) acc[b] = 0.f;
     fma_group<B, U>(g, xs, kpad, 0, nch, lane, acc);
     for (int it0 = U; it0 < nch; it0 += U) {
-        load_group<U>(g, row, live ? d : 0, it0, lane);
+        load_group<U>(g, row, it0, lane);
         fma_group<B, U>(g, xs, kpad, it0, nch, lane, acc);
     }
 #pragma unroll
@@ -100,6 +127,7 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
         const float s = wave_sum(acc[b]) * scale[b];
         if (live && lane == 0) t[(size_t)b * r + m] = fmaxf(s, 0.f);
     }
+    PF_TSTAMP(0, 2);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -117,15 +145,22 @@ __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
     __shared__ float logit_s[B][64];
     // 16 waves per block leave 128 VGPRs per lane: fewer loads in flight at larger batch
     constexpr int U = (B <= 2) ? 4 : 2, R = 64 / (kPredOutThreads / kWave);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = wave_uniform(threadIdx.x >> 6);
     const int nch = (r + kChunk - 1) / kChunk, kpad = nch * kChunk;
     const int n0 = blockIdx.x * 64 + wave * R;
+    rsrc_t rows[R];
+#pragma unroll
+    for (int q = 0; q < R; ++q) rows[q] = row_rsrc(p2, n0 + q, r, true);
 
+    PF_TSTAMP(1, 0);
+    Staged<B, 1> st;  // 1024 threads cover 4096 floats in one stride
+    stage_issue<B, 1>(st, t, r);
     WGroup<U> g[R];
 #pragma unroll
-    for (int q = 0; q < R; ++q) load_group<U>(g[q], p2 + (size_t)(n0 + q) * r, r, 0, lane);
-    stage_vector<B>(ts, t, r, kpad);
+    for (int q = 0; q < R; ++q) load_group<U>(g[q], rows[q], 0, lane);
+    stage_commit<B, 1>(st, ts, t, r, kpad);
     __syncthreads();
+    PF_TSTAMP(1, 1);
 
     float acc[R][B];
 #pragma unroll
@@ -136,7 +171,7 @@ __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
     }
     for (int it0 = U; it0 < nch; it0 += U) {
 #pragma unroll
-        for (int q = 0; q < R; ++q) load_group<U>(g[q], p2 + (size_t)(n0 + q) * r, r, it0, lane);
+        for (int q = 0; q < R; ++q) load_group<U>(g[q], rows[q], it0, lane);
 #pragma unroll
         for (int q = 0; q < R; ++q) fma_group<B, U>(g[q], ts, kpad, it0, nch, lane, acc[q]);
     }
@@ -164,6 +199,7 @@ __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
         const uint64_t word = __ballot(on);
         if (lane == 0) mask_words[blockIdx.x] = word;
     }
+    PF_TSTAMP(1, 2);
 }
 
 // ---------------------------------------------------------------------------------------

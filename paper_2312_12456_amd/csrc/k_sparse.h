@@ -46,9 +46,13 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
     const int nch = (d + kChunk - 1) / kChunk, kpad = nch * kChunk;
     const int stride = gridDim.x * kUpWaves;
     const int nwords = ffn / 64;
-    uint64_t *words_lds = reinterpret_cast<uint64_t *>(xs + (size_t)B * kpad);
+    uint64_t *words_lds = reinterpret_cast<uint64_t *>(xs + (size_t)B * kpad + kStageScrap);
     uint32_t *pre_lds = reinterpret_cast<uint32_t *>(words_lds + nwords);
 
+    PF_TSTAMP(2, 0);
+    constexpr int SS = (B >= 4) ? 1 : 4 / B;
+    Staged<B, SS> st;
+    stage_issue<B, SS>(st, x, d);  // in flight during the mask scan; lands before any weight
     int n;
     if (FROM_MASK) {
         n = (int)mask_prefix<kUpThreads>(mask_words, nwords, words_lds, pre_lds, wave_tot);
@@ -57,6 +61,7 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
         n = min(max(*count_in, 0), ffn);
     }
     if ((int)blockIdx.x * kUpWaves >= n) return;  // uniform over the block
+    PF_TSTAMP(2, 1);
 
     auto neuron_of = [&](int j) -> int {
         if (FROM_MASK) {
@@ -71,16 +76,20 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
     int i = 0;
     bool valid = false;
     if (j < n) {
-        i = neuron_of(j);
+        i = wave_uniform(neuron_of(j));
         valid = (unsigned)i < (unsigned)ffn;
         if (!valid) i = 0;
     }
+    PF_TSTAMP(2, 5);
     WGroup<U> gu, gg;
-    load_group<U>(gu, w_up + (size_t)i * d, valid ? d : 0, 0, lane);
-    if (GATED) load_group<U>(gg, w_gate + (size_t)i * d, valid ? d : 0, 0, lane);
+    rsrc_t ru = row_rsrc(w_up, i, d, valid), rg = row_rsrc(GATED ? w_gate : w_up, i, d, valid);
+    load_group<U>(gu, ru, 0, lane);
+    if (GATED) load_group<U>(gg, rg, 0, lane);
 
-    stage_vector<B>(xs, x, d, kpad);
+    PF_TSTAMP(2, 2);
+    stage_commit<B, SS>(st, xs, x, d, kpad);
     __syncthreads();
+    PF_TSTAMP(2, 3);
 
     while (j < n) {  // wave-uniform; no block-level synchronisation inside
         float au[B], ag[B];
@@ -89,8 +98,8 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
         fma_group<B, U>(gu, xs, kpad, 0, nch, lane, au);
         if (GATED) fma_group<B, U>(gg, xs, kpad, 0, nch, lane, ag);
         for (int it0 = U; it0 < nch; it0 += U) {
-            load_group<U>(gu, w_up + (size_t)i * d, valid ? d : 0, it0, lane);
-            if (GATED) load_group<U>(gg, w_gate + (size_t)i * d, valid ? d : 0, it0, lane);
+            load_group<U>(gu, ru, it0, lane);
+            if (GATED) load_group<U>(gg, rg, it0, lane);
             fma_group<B, U>(gu, xs, kpad, it0, nch, lane, au);
             if (GATED) fma_group<B, U>(gg, xs, kpad, it0, nch, lane, ag);
         }
@@ -98,11 +107,13 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
         const bool vcur = valid;
         j += stride;
         if (j < n) {  // next row in flight before this row's reductions
-            i = neuron_of(j);
+            i = wave_uniform(neuron_of(j));
             valid = (unsigned)i < (unsigned)ffn;
             if (!valid) i = 0;
-            load_group<U>(gu, w_up + (size_t)i * d, valid ? d : 0, 0, lane);
-            if (GATED) load_group<U>(gg, w_gate + (size_t)i * d, valid ? d : 0, 0, lane);
+            ru = row_rsrc(w_up, i, d, valid);
+            rg = row_rsrc(GATED ? w_gate : w_up, i, d, valid);
+            load_group<U>(gu, ru, 0, lane);
+            if (GATED) load_group<U>(gg, rg, 0, lane);
         }
         const float bias = (b_up != nullptr && vcur) ? b_up[icur] : 0.f;
 #pragma unroll
@@ -118,6 +129,7 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
             if (lane == 0) h[(size_t)b * ffn + jcur] = vcur ? v : 0.f;
         }
     }
+    PF_TSTAMP(2, 4);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -129,7 +141,13 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
 // belong to four workgroups with consecutive tile numbers; tiles are numbered so that
 // consecutive tiles run on the same XCD (workgroups are dealt round-robin to the 8 XCDs),
 // hence every line is fetched from HBM once, into one L2.
-constexpr int kDownThreads = 512;
+#ifndef PF_DOWN_THREADS
+#define PF_DOWN_THREADS 512
+#endif
+#ifndef PF_DOWN_U
+#define PF_DOWN_U 8
+#endif
+constexpr int kDownThreads = PF_DOWN_THREADS;
 constexpr int kDownWaves = kDownThreads / kWave;
 constexpr int kDownCols = 16;
 constexpr int kDownRowsPerLoad = kDownThreads / 2;  // rows one load instruction of the block covers
@@ -142,18 +160,21 @@ __global__ __launch_bounds__(kDownThreads) void k_down(
     const float *__restrict__ h, const int32_t *__restrict__ idx,
     const int32_t *__restrict__ count_p, float *__restrict__ y, int d, int ffn, int ntiles)
 {
-    constexpr int U = (B <= 2) ? 8 : 4;
+    constexpr int U = (B <= 2) ? PF_DOWN_U : 4;
     constexpr int STEP = kDownRowsPerLoad * U;
     __shared__ float red[kDownWaves][B][kDownCols];
     // tile <-> block: blocks b, b+8, b+16, ... (same XCD) take consecutive tiles
     const int per_xcd = (ntiles + 7) >> 3;
     const int tile = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
     if (tile >= ntiles) return;  // uniform over the block
+    PF_TSTAMP(3, 0);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5;                 // which 16 bytes of the 32-byte run
     const int rlane = wave * 32 + (lane & 31);  // row slot of this lane inside a load
     const int col = tile * kDownCols + half * 8;
     const bool colok = col < d;
+
+    const rsrc_t wd = make_rsrc(w_down, (uint32_t)ffn * (uint32_t)d * 2u);
 
     float acc[B][8];
 #pragma unroll
@@ -180,16 +201,19 @@ __global__ __launch_bounds__(kDownThreads) void k_down(
             n = min(max(*count_p, 0), ffn);
             have_n = true;
         }
+#ifdef PF_TRACE
+        if (threadIdx.x == 0 && n == -12345) y[0] = 0.f;  // forces the count to have arrived
+#endif
+        PF_TSTAMP(3, 4);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int jj = j0 + u * kDownRowsPerLoad + rlane;
             bool ok = jj < n;
             if (!SPEC) iv[u] = ok ? idx[jj] : 0;
             ok = ok && (unsigned)iv[u] < (unsigned)ffn;
-            if (ok && colok)
-                w[u] = ld16_stream(w_down + (size_t)iv[u] * d + col);
-            else
-                w[u] = make_uint4(0u, 0u, 0u, 0u);
+            w[u] = ld16_stream(wd, (ok && colok) ? ((uint32_t)iv[u] * (uint32_t)d + (uint32_t)col) * 2u
+                                                 : kOobOffset);
+            if (u == 0) PF_TSTAMP(3, 5);
 #pragma unroll
             for (int b = 0; b < B; ++b) {
                 if (SPEC)
@@ -198,6 +222,7 @@ __global__ __launch_bounds__(kDownThreads) void k_down(
                     hv[u][b] = ok ? h[(size_t)b * ffn + jj] : 0.f;
             }
         }
+        PF_TSTAMP(3, 1);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const float f0 = h_lo(w[u].x), f1 = h_hi(w[u].x), f2 = h_lo(w[u].y), f3 = h_hi(w[u].y);
@@ -217,6 +242,7 @@ __global__ __launch_bounds__(kDownThreads) void k_down(
         }
     }
 
+    PF_TSTAMP(3, 2);
     // sum over the 32 row slots of each half-wave: 16 lanes by DPP, then the two rows of 16
 #pragma unroll
     for (int b = 0; b < B; ++b) {
@@ -242,6 +268,7 @@ __global__ __launch_bounds__(kDownThreads) void k_down(
             y[(size_t)b * d + oc] = s;
         }
     }
+    PF_TSTAMP(3, 3);
 }
 
 // ---------------------------------------------------------------------------------------

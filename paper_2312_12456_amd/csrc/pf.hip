@@ -197,7 +197,7 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
     const int tile = batch_tile(ctx, D.d, B, 1024);
     for (int b0 = 0; b0 < B; b0 += tile) {
         const int bt = (B - b0) < tile ? (B - b0) : tile;
-        const size_t lds = (size_t)bt * kpad_of(D.d) * sizeof(float);
+        const size_t lds = ((size_t)bt * kpad_of(D.d) + pf::kStageScrap) * sizeof(float);
         const dim3 grid(cdiv(D.r, pf::kPredWaves));
         const size_t xo = (size_t)b0 * D.d;
         ProfScope ps(ctx, K_PRED_HIDDEN);
@@ -214,7 +214,7 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
         }
     }
     // output layer over the whole batch (its staged vector is only B * r floats)
-    const size_t lds = (size_t)B * kpad_of(D.r) * sizeof(float);
+    const size_t lds = ((size_t)B * kpad_of(D.r) + pf::kStageScrap) * sizeof(float);
     const dim3 grid(D.ffn / 64);
     {
         ProfScope ps(ctx, K_PRED_OUT);
@@ -244,7 +244,7 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     const bool gated = D.act == PF_ACT_REGLU;
     for (int b0 = 0; b0 < B; b0 += tile) {
         const int bt = (B - b0) < tile ? (B - b0) : tile;
-        const size_t lds = (size_t)bt * kpad_of(D.d) * sizeof(float) + extra;
+        const size_t lds = ((size_t)bt * kpad_of(D.d) + pf::kStageScrap) * sizeof(float) + extra;
         const float *xb = x + (size_t)b0 * D.d;
         float *hb = ctx->h + (size_t)b0 * D.ffn;
         ProfScope ps(ctx, K_UP);
@@ -445,6 +445,9 @@ pf_status pf_layer_create(pf_ctx *ctx, const pf_layer_desc *desc, const pf_layer
     if (desc->d > ctx->max_d || desc->ffn > ctx->max_ffn || desc->r > ctx->max_r)
         return fail(ctx, PF_ESHAPE, "layer (d=%d, ffn=%d, r=%d) exceeds context (%d, %d, %d)",
                     desc->d, desc->ffn, desc->r, ctx->max_d, ctx->max_ffn, ctx->max_r);
+    // kernels address a matrix through a 32-bit buffer descriptor
+    if ((uint64_t)desc->ffn * desc->d * 2 >= (1ull << 32) || (uint64_t)desc->ffn * desc->r * 2 >= (1ull << 32))
+        return fail(ctx, PF_ESHAPE, "a weight matrix of 4 GiB or more is not supported");
     if (!w->w_up || !w->w_down) return fail(ctx, PF_EINVAL, "w_up / w_down is null");
     if (desc->act == PF_ACT_REGLU && !w->w_gate) return fail(ctx, PF_EINVAL, "gated layer without w_gate");
     if ((w->p1 == nullptr) != (w->p2 == nullptr))
@@ -624,6 +627,17 @@ pf_status pf_profile_end(pf_ctx *ctx, pf_kernel_stat *stats, int capacity, int *
     ctx->prof_kernel.clear();
     return PF_OK;
 }
+
+#ifdef PF_TRACE
+// Tuning builds only: device buffer of [4 kernels][4096 blocks][8] 64-bit stamps, or NULL.
+pf_status pf_debug_set_trace(unsigned long long *device_buffer)
+{
+    return hipMemcpyToSymbol(HIP_SYMBOL(pf::g_pf_trace), &device_buffer, sizeof(device_buffer)) ==
+                   hipSuccess
+               ? PF_OK
+               : PF_EHIP;
+}
+#endif
 
 const char *pf_strerror(pf_status s)
 {

@@ -10,7 +10,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libpf.so")
+# PF_LIB_PATH selects another build of the same library (kernel tuning experiments)
+LIB_PATH = os.environ.get("PF_LIB_PATH") or os.path.join(_HERE, "libpf.so")
 
 PF_OK, PF_EINVAL, PF_ESHAPE, PF_ENOMEM, PF_EHIP, PF_EUNSUPPORTED = range(6)
 ACT_RELU, ACT_REGLU = 0, 1
