@@ -13,7 +13,7 @@ constexpr int kChunk = 512;    // elements of a row one wave covers per 16-byte 
 // Phase timestamps for kernel tuning, compiled in only with -DPF_TRACE: thread 0 of a block
 // stores the 100 MHz wall clock at a few program points into a host-provided buffer.
 #ifdef PF_TRACE
-__device__ unsigned long long *g_pf_trace = nullptr;  // [slot][4096 blocks][8 stamps]
+__constant__ unsigned long long *g_pf_trace = nullptr;  // [slot][4096 blocks][8 stamps]
 #define PF_TSTAMP(slot, k)                                                                   \
     do {                                                                                     \
         if (threadIdx.x == 0 && g_pf_trace && blockIdx.x < 4096)                             \

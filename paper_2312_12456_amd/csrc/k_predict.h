@@ -131,10 +131,19 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
 }
 
 // ---------------------------------------------------------------------------------------
-// Output layer + threshold + ballot.  grid = ffn / 64; block g (16 waves) owns neurons
-// 64g .. 64g+63, wave w of it rows 4w .. 4w+3, all in flight at once; wave 0 turns the 64
-// decisions into one mask word with a ballot.
-constexpr int kPredOutThreads = 1024;
+// Output layer + threshold + ballot.  grid = ffn / NB; block g owns the NB neurons from
+// NB*g on (NB = 16, 32 or 64: a quarter, half or whole mask word), wave w of it rows
+// 4w .. 4w+3, all in flight at once; wave 0 turns the NB decisions into its piece of the
+// mask word with a ballot.
+#ifndef PF_OUT_NEURONS
+#define PF_OUT_NEURONS 64
+#endif
+constexpr int kPredOutNeurons = PF_OUT_NEURONS;
+constexpr int kPredOutThreads = kPredOutNeurons * 16;
+static_assert(kPredOutNeurons == 16 || kPredOutNeurons == 32 || kPredOutNeurons == 64, "mask piece");
+template <int NB> struct MaskPiece { typedef uint64_t type; };
+template <> struct MaskPiece<32> { typedef uint32_t type; };
+template <> struct MaskPiece<16> { typedef uint16_t type; };
 
 template <int B>
 __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
@@ -142,24 +151,31 @@ __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
     int r, int ffn, float thr_logit, float *__restrict__ scores, uint64_t *__restrict__ mask_words)
 {
     extern __shared__ float ts[];  // [B][kpad] staged hidden vector
-    __shared__ float logit_s[B][64];
+    constexpr int NB = kPredOutNeurons;
+    __shared__ float logit_s[B][NB];
     // 16 waves per block leave 128 VGPRs per lane: fewer loads in flight at larger batch
-    constexpr int U = (B <= 2) ? 4 : 2, R = 64 / (kPredOutThreads / kWave);
+    constexpr int U = (B <= 2) ? 4 : 2, R = NB / (kPredOutThreads / kWave);
+    constexpr int SS = (kPredOutThreads >= 1024 || B >= 4) ? 1 : 4 / B;
     const int lane = threadIdx.x & 63, wave = wave_uniform(threadIdx.x >> 6);
     const int nch = (r + kChunk - 1) / kChunk, kpad = nch * kChunk;
-    const int n0 = blockIdx.x * 64 + wave * R;
+    const int n0 = blockIdx.x * NB + wave * R;
     rsrc_t rows[R];
 #pragma unroll
     for (int q = 0; q < R; ++q) rows[q] = row_rsrc(p2, n0 + q, r, true);
 
     PF_TSTAMP(1, 0);
-    Staged<B, 1> st;  // 1024 threads cover 4096 floats in one stride
-    stage_issue<B, 1>(st, t, r);
+    Staged<B, SS> st;
+    stage_issue<B, SS>(st, t, r);
+#ifndef PF_OUT_PRE
+#define PF_OUT_PRE 2  // rows whose loads are issued before the block barrier
+#endif
     WGroup<U> g[R];
 #pragma unroll
-    for (int q = 0; q < R; ++q) load_group<U>(g[q], rows[q], 0, lane);
-    stage_commit<B, 1>(st, ts, t, r, kpad);
+    for (int q = 0; q < PF_OUT_PRE; ++q) load_group<U>(g[q], rows[q], 0, lane);
+    stage_commit<B, SS>(st, ts, t, r, kpad);
     __syncthreads();
+#pragma unroll
+    for (int q = PF_OUT_PRE; q < R; ++q) load_group<U>(g[q], rows[q], 0, lane);
     PF_TSTAMP(1, 1);
 
     float acc[R][B];
@@ -187,17 +203,18 @@ __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
     __syncthreads();
 
     if (scores != nullptr) {
-        for (int e = threadIdx.x; e < B * 64; e += kPredOutThreads) {
-            const int b = e >> 6, q = e & 63;
-            scores[(size_t)b * ffn + blockIdx.x * 64 + q] = 1.f / (1.f + __expf(-logit_s[b][q]));
+        for (int e = threadIdx.x; e < B * NB; e += kPredOutThreads) {
+            const int b = e / NB, q = e % NB;
+            scores[(size_t)b * ffn + blockIdx.x * NB + q] = 1.f / (1.f + __expf(-logit_s[b][q]));
         }
     }
     if (wave == 0) {
         bool on = false;
 #pragma unroll
-        for (int b = 0; b < B; ++b) on = on || (logit_s[b][lane] > thr_logit);
+        for (int b = 0; b < B; ++b) on = on || (lane < NB && logit_s[b][lane % NB] > thr_logit);
         const uint64_t word = __ballot(on);
-        if (lane == 0) mask_words[blockIdx.x] = word;
+        typedef typename MaskPiece<NB>::type piece_t;  // little endian: piece g of the words
+        if (lane == 0) reinterpret_cast<piece_t *>(mask_words)[blockIdx.x] = (piece_t)word;
     }
     PF_TSTAMP(1, 2);
 }

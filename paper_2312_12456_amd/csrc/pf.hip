@@ -15,6 +15,7 @@
 
 #include "k_predict.h"
 #include "k_sparse.h"
+#include "k_fused.h"
 
 namespace {
 
@@ -24,9 +25,12 @@ constexpr int kProfPairsCap = 32768;    // event pairs one profiling pass may re
 constexpr int kLdsMax = 160 * 1024;     // LDS per workgroup on gfx950
 constexpr int kLdsDefault = 64 * 1024;  // what a kernel may use without opting in
 
-enum KernelId { K_PRED_HIDDEN = 0, K_PRED_OUT, K_COMPACT, K_UP, K_DOWN, K_GLUE, K_NUM };
-const char *const kKernelNames[K_NUM] = {"k_pred_hidden", "k_pred_out", "k_compact",
-                                         "k_up", "k_down", "k_glue"};
+enum KernelId {
+    K_PRED_HIDDEN = 0, K_PRED_OUT, K_COMPACT, K_UP, K_DOWN, K_GLUE, K_OUT_UP, K_DOWN_MASK, K_NUM
+};
+const char *const kKernelNames[K_NUM] = {"k_pred_hidden", "k_pred_out", "k_compact", "k_up",
+                                         "k_down",        "k_glue",     "k_pred_out_up",
+                                         "k_down_mask"};
 
 }  // namespace
 
@@ -36,6 +40,7 @@ struct pf_ctx {
     int num_cu = 256;
     int up_grid_cap = 2048;
     int lds_budget = kLdsDefault;  // dynamic LDS a kernel of this context may request
+    bool no_fused = true;          // PF_FUSED=1 selects the three-launch layer step (k_fused.h)
     // scratch (device)
     float *t = nullptr;              // [max_batch][max_r] predictor hidden vector
     uint64_t *mask_words = nullptr;  // [max_ffn / 64]
@@ -128,6 +133,8 @@ hipError_t allow_lds_for_batch()
     if (e == hipSuccess) e = allow_lds(pf::k_up<B, 1, false>);
     if (e == hipSuccess) e = allow_lds(pf::k_up<B, 0, true>);
     if (e == hipSuccess) e = allow_lds(pf::k_up<B, 1, true>);
+    if (e == hipSuccess) e = allow_lds(pf::k_pred_out_up<B, 0>);
+    if (e == hipSuccess) e = allow_lds(pf::k_pred_out_up<B, 1>);
     return e;
 }
 
@@ -184,15 +191,14 @@ struct ProfScope {
     } while (0)
 
 // ---- launches ------------------------------------------------------------------------
-// Predictor: hidden layer then output layer + ballot.  With glue_y the layer input is
-// formed inside the hidden kernel as norm(x + glue_y) and also written to x_new.
-pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
-                         float *x_new, int B, float *scores, uint64_t *mask_words, hipStream_t st)
+// Predictor hidden layer.  With glue_y the layer input is formed inside the kernel as
+// norm(x + glue_y) and also written to x_new.
+pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
+                        float *x_new, int B, hipStream_t st)
 {
     const pf_layer_desc &D = L->desc;
     if (!L->w.p1 || !L->w.p2) return fail(ctx, PF_EINVAL, "layer has no predictor weights");
     const __half *p1 = static_cast<const __half *>(L->w.p1);
-    const __half *p2 = static_cast<const __half *>(L->w.p2);
     // hidden layer, in batch tiles that fit LDS
     const int tile = batch_tile(ctx, D.d, B, 1024);
     for (int b0 = 0; b0 < B; b0 += tile) {
@@ -213,9 +219,21 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
                                                ctx->t + (size_t)b0 * D.r, D.d, D.r));
         }
     }
+    PF_HIP(ctx, hipGetLastError());
+    return PF_OK;
+}
+
+// Predictor: hidden layer, then output layer + ballot into mask words.
+pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
+                         float *x_new, int B, float *scores, uint64_t *mask_words, hipStream_t st)
+{
+    pf_status s = launch_hidden(ctx, L, x, glue_y, x_new, B, st);
+    if (s != PF_OK) return s;
+    const pf_layer_desc &D = L->desc;
+    const __half *p2 = static_cast<const __half *>(L->w.p2);
     // output layer over the whole batch (its staged vector is only B * r floats)
     const size_t lds = ((size_t)B * kpad_of(D.r) + pf::kStageScrap) * sizeof(float);
-    const dim3 grid(D.ffn / 64);
+    const dim3 grid(D.ffn / pf::kPredOutNeurons);
     {
         ProfScope ps(ctx, K_PRED_OUT);
         PF_SWITCH_B(B, PF_LAUNCH(ps, pf::k_pred_out<BT>, grid, dim3(pf::kPredOutThreads), lds,
@@ -279,6 +297,56 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     return PF_OK;
 }
 
+// Whole layer step.  Three launches when the fused kernel's LDS image fits (hidden layer;
+// output layer + FC1 of each block's own active neurons; FC2 with in-kernel compaction),
+// otherwise predictor, FC1 with fused compaction and FC2.  x_in is the layer input as the
+// later kernels see it: x itself, or x_new when the hidden kernel forms it (glue_y given).
+pf_status launch_layer(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
+                       float *x_new, int B, float *y, hipStream_t st)
+{
+    const pf_layer_desc &D = L->desc;
+    const float *x_in = glue_y ? x_new : x;
+    const size_t fused_lds = pf::out_up_lds_bytes(B, D.r, D.d);
+    const bool fused = !ctx->no_fused && fused_lds + 1024 <= (size_t)ctx->lds_budget &&
+                       pf::down_mask_lds_bytes(D.ffn) + 8192 <= (size_t)kLdsDefault;
+    if (!fused) {
+        pf_status s = launch_predict(ctx, L, x, glue_y, x_new, B, nullptr, ctx->mask_words, st);
+        if (s != PF_OK) return s;
+        return launch_sparse(ctx, L, x_in, B, nullptr, nullptr, ctx->mask_words, y, st);
+    }
+    pf_status s = launch_hidden(ctx, L, x, glue_y, x_new, B, st);
+    if (s != PF_OK) return s;
+    const __half *p2 = static_cast<const __half *>(L->w.p2);
+    const __half *w_up = static_cast<const __half *>(L->w.w_up);
+    const __half *w_gate = static_cast<const __half *>(L->w.w_gate);
+    const __half *w_down = static_cast<const __half *>(L->w.w_down);
+    {
+        ProfScope ps(ctx, K_OUT_UP);
+        const dim3 grid(D.ffn / 64);
+        if (D.act == PF_ACT_REGLU) {
+            PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_pred_out_up<BT, 1>), grid, dim3(pf::kOutUpThreads),
+                                     fused_lds, st, p2, L->w.p_bias, ctx->t, w_up, w_gate,
+                                     L->w.b_up, x_in, D.r, D.d, D.ffn, L->thr_logit,
+                                     ctx->mask_words, ctx->h));
+        } else {
+            PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_pred_out_up<BT, 0>), grid, dim3(pf::kOutUpThreads),
+                                     fused_lds, st, p2, L->w.p_bias, ctx->t, w_up, w_gate,
+                                     L->w.b_up, x_in, D.r, D.d, D.ffn, L->thr_logit,
+                                     ctx->mask_words, ctx->h));
+        }
+    }
+    {
+        ProfScope ps(ctx, K_DOWN_MASK);
+        const int ntiles = cdiv(D.d, pf::kDownCols);
+        const dim3 grid(cdiv(ntiles, 8) * 8);
+        PF_SWITCH_B(B, PF_LAUNCH(ps, pf::k_down_mask<BT>, grid, dim3(pf::kDownThreads),
+                                 pf::down_mask_lds_bytes(D.ffn), st, w_down, L->w.b_down, ctx->h,
+                                 ctx->mask_words, ctx->idx, ctx->count, y, D.d, D.ffn, ntiles));
+    }
+    PF_HIP(ctx, hipGetLastError());
+    return PF_OK;
+}
+
 pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int d, int B, float *x_next,
                       hipStream_t st)
 {
@@ -301,14 +369,12 @@ pf_status stack_enqueue(pf_ctx *ctx, pf_layer *const *layers, int n_layers, cons
         const pf_layer *L = layers[l];
         pf_status s;
         if (l == 0) {
-            s = launch_predict(ctx, L, cur, nullptr, nullptr, B, nullptr, ctx->mask_words, st);
+            s = launch_layer(ctx, L, cur, nullptr, nullptr, B, ctx->ybuf, st);
         } else {
             float *xn = ctx->xbuf[l & 1];
-            s = launch_predict(ctx, L, cur, ctx->ybuf, xn, B, nullptr, ctx->mask_words, st);
+            s = launch_layer(ctx, L, cur, ctx->ybuf, xn, B, ctx->ybuf, st);
             cur = xn;
         }
-        if (s != PF_OK) return s;
-        s = launch_sparse(ctx, L, cur, B, nullptr, nullptr, ctx->mask_words, ctx->ybuf, st);
         if (s != PF_OK) return s;
     }
     return launch_glue(ctx, cur, ctx->ybuf, layers[0]->desc.d, B, x_out, st);
@@ -364,6 +430,7 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         if (e != hipSuccess) { st = PF_EHIP; break; }
         if (prop.multiProcessorCount > 0) ctx->num_cu = prop.multiProcessorCount;
         ctx->up_grid_cap = 8 * ctx->num_cu;
+        if (const char *v = getenv("PF_FUSED")) ctx->no_fused = atoi(v) == 0;
         if (const char *v = getenv("PF_UP_GRID")) {
             int c = atoi(v);
             if (c >= 1 && c <= 65535) ctx->up_grid_cap = c;
@@ -511,10 +578,8 @@ pf_status pf_layer_step(pf_ctx *ctx, const pf_layer *layer, const float *x, int 
     pf_status s = check_batch(ctx, layer, x, B);
     if (s != PF_OK) return s;
     if (!y) return fail(ctx, PF_EINVAL, "y is null");
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    s = launch_predict(ctx, layer, x, nullptr, nullptr, B, nullptr, ctx->mask_words, st);
-    if (s != PF_OK) return s;
-    return launch_sparse(ctx, layer, x, B, nullptr, nullptr, ctx->mask_words, y, st);
+    if (!layer->w.p1) return fail(ctx, PF_EINVAL, "layer has no predictor weights");
+    return launch_layer(ctx, layer, x, nullptr, nullptr, B, y, static_cast<hipStream_t>(stream));
 }
 
 pf_status pf_ctx_last_active(pf_ctx *ctx, const uint64_t **mask_words, const int32_t **idx,
