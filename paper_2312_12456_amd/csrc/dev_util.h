@@ -138,6 +138,17 @@ __device__ __forceinline__ int lds_slot(int e)
     return (e & ~511) + (((e & 7) >> 2) << 8) + (((e & 511) >> 3) << 2) + (e & 3);
 }
 
+// The same idea for a lane that consumes EPL consecutive elements per 16-byte weight load
+// (8 for fp16, 32 for int4): a chunk is 64 * EPL elements, split into EPL / 4 planes of 256
+// floats, plane p holding float4 number p of every lane.
+template <int EPL>
+__device__ __forceinline__ int lds_slot_epl(int e)
+{
+    constexpr int W = 64 * EPL;
+    const int r = e & (W - 1), q = r & (EPL - 1);
+    return (e & ~(W - 1)) + ((q >> 2) << 8) + ((r / EPL) << 2) + (q & 3);
+}
+
 // Cooperative copy of v[B][K] (global fp32) into the LDS layout above, zero padded to kpad,
 // in two phases so that the caller can put other work between them: stage_issue puts the
 // global loads of the first pass in flight (S strides x B tokens per thread, kept in
@@ -169,7 +180,7 @@ __device__ __forceinline__ void stage_issue(Staged<B, S> &st, const float *__res
     }
 }
 
-template <int B, int S>
+template <int B, int S, int EPL = 8>
 __device__ __forceinline__ void stage_commit(const Staged<B, S> &st, float *__restrict__ xs,
                                              const float *__restrict__ v, int K, int kpad)
 {
@@ -180,7 +191,7 @@ __device__ __forceinline__ void stage_commit(const Staged<B, S> &st, float *__re
         const int e = threadIdx.x * 4 + s * step;
 #pragma unroll
         for (int b = 0; b < B; ++b)
-            *reinterpret_cast<float4 *>(xs + (e < kpad ? b * kpad + lds_slot(e) : scrap)) =
+            *reinterpret_cast<float4 *>(xs + (e < kpad ? b * kpad + lds_slot_epl<EPL>(e) : scrap)) =
                 st.val[s][b];
     }
     const rsrc_t r = make_rsrc(v, (uint32_t)B * (uint32_t)K * 4u);
@@ -198,7 +209,7 @@ __device__ __forceinline__ void stage_commit(const Staged<B, S> &st, float *__re
             const int e = e0 + s * step;
 #pragma unroll
             for (int b = 0; b < B; ++b)
-                *reinterpret_cast<float4 *>(xs + (e < kpad ? b * kpad + lds_slot(e) : scrap)) =
+                *reinterpret_cast<float4 *>(xs + (e < kpad ? b * kpad + lds_slot_epl<EPL>(e) : scrap)) =
                     val[s][b];
         }
     }

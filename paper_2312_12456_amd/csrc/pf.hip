@@ -16,6 +16,7 @@
 #include "k_predict.h"
 #include "k_sparse.h"
 #include "k_fused.h"
+#include "k_int4.h"
 
 namespace {
 
@@ -135,6 +136,10 @@ hipError_t allow_lds_for_batch()
     if (e == hipSuccess) e = allow_lds(pf::k_up<B, 1, true>);
     if (e == hipSuccess) e = allow_lds(pf::k_pred_out_up<B, 0>);
     if (e == hipSuccess) e = allow_lds(pf::k_pred_out_up<B, 1>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_i4<B, 0, false>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_i4<B, 1, false>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_i4<B, 0, true>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_i4<B, 1, true>);
     return e;
 }
 
@@ -244,6 +249,67 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
     return PF_OK;
 }
 
+inline int kpad_i4(int k) { return cdiv(k, pf::kI4Chunk) * pf::kI4Chunk; }
+
+// Sparse FFN over int4 weights (same launch structure as the fp16 one below).
+pf_status launch_sparse_i4(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
+                           const int32_t *idx_in, const int32_t *count_in,
+                           const uint64_t *mask_words, float *y, hipStream_t st)
+{
+    const pf_layer_desc &D = L->desc;
+    const uint8_t *q_up = static_cast<const uint8_t *>(L->w.w_up);
+    const uint8_t *q_gate = static_cast<const uint8_t *>(L->w.w_gate);
+    const uint8_t *q_down = static_cast<const uint8_t *>(L->w.w_down);
+    const __half *s_up = static_cast<const __half *>(L->w.s_up);
+    const __half *s_gate = static_cast<const __half *>(L->w.s_gate);
+    const __half *s_down = static_cast<const __half *>(L->w.s_down);
+    const bool from_mask = mask_words != nullptr;
+    const size_t extra = from_mask ? pf::up_mask_lds_bytes(D.ffn) : 0;
+    const size_t per_tok = (size_t)kpad_i4(D.d) * sizeof(float);
+    int tile = (int)(((size_t)ctx->lds_budget - extra - 1024) / per_tok);
+    if (tile > kMaxBatch) tile = kMaxBatch;
+    if (tile < 1) tile = 1;
+    if (tile > B) tile = B;
+    int up_grid = cdiv(D.ffn, pf::kUpI4Waves);
+    if (up_grid > ctx->up_grid_cap) up_grid = ctx->up_grid_cap;
+    const bool gated = D.act == PF_ACT_REGLU;
+    for (int b0 = 0; b0 < B; b0 += tile) {
+        const int bt = (B - b0) < tile ? (B - b0) : tile;
+        const size_t lds = (size_t)bt * per_tok + pf::kStageScrap * sizeof(float) + extra;
+        const float *xb = x + (size_t)b0 * D.d;
+        float *hb = ctx->h + (size_t)b0 * D.ffn;
+        ProfScope ps(ctx, K_UP);
+#define PF_UP4(ACT, FM)                                                                           \
+    PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_up_i4<BT, ACT, FM>), dim3(up_grid),                      \
+                              dim3(pf::kUpI4Threads), lds, st, q_up, s_up, q_gate, s_gate,        \
+                              L->w.b_up, xb, idx_in, count_in, mask_words, ctx->idx, ctx->count,  \
+                              hb, D.d, D.ffn))
+        if (gated && from_mask) { PF_UP4(1, true); }
+        else if (gated) { PF_UP4(1, false); }
+        else if (from_mask) { PF_UP4(0, true); }
+        else { PF_UP4(0, false); }
+#undef PF_UP4
+    }
+    const int32_t *idx = from_mask ? ctx->idx : idx_in;
+    const int32_t *count = from_mask ? ctx->count : count_in;
+    const int ntiles = cdiv(D.d, pf::kDownI4Cols);
+    const dim3 grid(cdiv(ntiles, 8) * 8);
+    {
+        ProfScope ps(ctx, K_DOWN);
+        if (from_mask) {
+            PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_down_i4<BT, true>), grid, dim3(pf::kDownI4Threads),
+                                     0, st, q_down, s_down, L->w.b_down, ctx->h, idx, count, y,
+                                     D.d, D.ffn, ntiles));
+        } else {
+            PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_down_i4<BT, false>), grid,
+                                     dim3(pf::kDownI4Threads), 0, st, q_down, s_down, L->w.b_down,
+                                     ctx->h, idx, count, y, D.d, D.ffn, ntiles));
+        }
+    }
+    PF_HIP(ctx, hipGetLastError());
+    return PF_OK;
+}
+
 // Sparse FFN.  Either an index list is given (idx_in, count_in) or mask words, from which
 // the FC1 kernel derives the list itself and leaves it in ctx->idx / ctx->count.
 pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
@@ -251,6 +317,8 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
                         const uint64_t *mask_words, float *y, hipStream_t st)
 {
     const pf_layer_desc &D = L->desc;
+    if (D.wtype == PF_W_INT4_G128)
+        return launch_sparse_i4(ctx, L, x, B, idx_in, count_in, mask_words, y, st);
     const __half *w_up = static_cast<const __half *>(L->w.w_up);
     const __half *w_gate = static_cast<const __half *>(L->w.w_gate);
     const __half *w_down = static_cast<const __half *>(L->w.w_down);
@@ -307,7 +375,8 @@ pf_status launch_layer(pf_ctx *ctx, const pf_layer *L, const float *x, const flo
     const pf_layer_desc &D = L->desc;
     const float *x_in = glue_y ? x_new : x;
     const size_t fused_lds = pf::out_up_lds_bytes(B, D.r, D.d);
-    const bool fused = !ctx->no_fused && fused_lds + 1024 <= (size_t)ctx->lds_budget &&
+    const bool fused = !ctx->no_fused && D.wtype == PF_W_FP16 &&
+                       fused_lds + 1024 <= (size_t)ctx->lds_budget &&
                        pf::down_mask_lds_bytes(D.ffn) + 8192 <= (size_t)kLdsDefault;
     if (!fused) {
         pf_status s = launch_predict(ctx, L, x, glue_y, x_new, B, nullptr, ctx->mask_words, st);
@@ -408,10 +477,10 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
     if (max_d < 1 || max_ffn < 1 || max_r < 1 || max_batch < 1 || max_batch > kMaxBatch || device < 0)
         return PF_EINVAL;
     if (max_ffn % 64 != 0 || max_d % 8 != 0 || max_r % 8 != 0 || max_ffn > kMaxFfn) return PF_ESHAPE;
-    // the staged hidden vector of the whole batch, and one staged token next to the mask
-    // words of the widest layer, must fit the LDS a kernel gets without opting in
+    // the staged hidden vector of the whole batch, and one staged token (padded to an int4
+    // chunk) next to the mask words of the widest layer, must fit LDS
     if ((size_t)max_batch * kpad_of(max_r) * sizeof(float) > (size_t)kLdsDefault - 2048 ||
-        (size_t)kpad_of(max_d) * sizeof(float) + pf::up_mask_lds_bytes(max_ffn) + 1024 >
+        (size_t)kpad_i4(max_d) * sizeof(float) + pf::up_mask_lds_bytes(max_ffn) + 1024 >
             (size_t)kLdsMax)
         return PF_ESHAPE;
     pf_ctx *ctx = new (std::nothrow) pf_ctx();
@@ -443,7 +512,7 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
             else
                 (void)hipGetLastError();
         }
-        if ((size_t)kpad_of(max_d) * sizeof(float) + pf::up_mask_lds_bytes(max_ffn) + 1024 >
+        if ((size_t)kpad_i4(max_d) * sizeof(float) + pf::up_mask_lds_bytes(max_ffn) + 1024 >
             (size_t)ctx->lds_budget) {
             st = PF_ESHAPE;
             break;
@@ -522,7 +591,6 @@ pf_status pf_layer_create(pf_ctx *ctx, const pf_layer_desc *desc, const pf_layer
     if (desc->wtype == PF_W_INT4_G128) {
         if (!w->s_up || !w->s_down || (desc->act == PF_ACT_REGLU && !w->s_gate))
             return fail(ctx, PF_EINVAL, "int4 layer without scales");
-        return fail(ctx, PF_EUNSUPPORTED, "int4 weights are not built yet");
     }
     pf_layer *L = new (std::nothrow) pf_layer();
     if (!L) return fail(ctx, PF_ENOMEM, "host allocation failed");

@@ -36,6 +36,7 @@ def _mask_of(pf, ctx, ffn):
     ("opt-6.7b", 1, 0), ("opt-6.7b", 1, 31),
     ("llama2-13b-reglu", 1, 0), ("llama2-13b-reglu", 4, 20),
     ("opt-30b", 1, 0), ("opt-30b", 8, 47),
+    ("opt-175b-int4", 1, 0), ("opt-175b-int4", 1, 95),
 ])
 def test_full_shape_layer_step(pf, oracle, name, B, layer):
     cfg = wl.CONFIGS[name]

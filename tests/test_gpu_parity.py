@@ -283,3 +283,51 @@ def test_argument_errors_reach_the_caller(pf):
     with pytest.raises(pf.PfError) as e:
         pf.Layer(ctx, 520, 1344, 136, act=pf.ACT_REGLU, w_up=lay["w_up"], w_down=lay["w_down"])
     assert e.value.status == pf.PF_EINVAL
+
+
+INT4_SHAPES = [
+    # d % 128 == 0; 640 = a third of one 2048-element chunk, 2304 = one chunk + a ragged second
+    dict(d=640, ffn=1344, r=136),
+    dict(d=2304, ffn=2048, r=264),
+]
+
+
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
+@pytest.mark.parametrize("shape", INT4_SHAPES)
+@pytest.mark.parametrize("B", [1, 3])
+def test_int4_exact_mask_and_layer_step(pf, oracle, act, shape, B):
+    """int4 group-128 weights dequantised in the kernels: both the list-driven FFN and the
+    whole layer step against the oracle, which reads the same packed bytes."""
+    cfg = small_cfg(rate=0.12, act=act, wtype=wl.W_INT4_G128, **shape)
+    ctx, L, O, lay = _setup(pf, cfg, seed=400 + B + act)
+    x = wl.make_inputs(cfg, 0, seed=6, batch=B, device="cuda")
+    xh = x.cpu().numpy()
+    mask = O.exact_mask(xh)
+    ref_idx = oracle.compact(mask)
+    idx = torch.zeros(cfg.ffn, dtype=torch.int32, device="cuda")
+    idx[:ref_idx.size] = torch.from_numpy(ref_idx).cuda()
+    count = torch.tensor([ref_idx.size], dtype=torch.int32, device="cuda")
+    y = torch.full((B, cfg.d), float("nan"), device="cuda")
+    ctx.sparse_ffn(L, x, idx, count, y)
+    torch.cuda.synchronize()
+    check_output(y.cpu().numpy(), O.masked_ffn(xh, mask), "int4 exact mask")
+    check_output(y.cpu().numpy(), O.dense_ffn(xh), "int4 exact mask vs dense")
+    # empty list
+    ctx.sparse_ffn(L, x, idx, torch.zeros(1, dtype=torch.int32, device="cuda"), y)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy().astype(np.float64),
+                          O.masked_ffn(xh, np.zeros(cfg.ffn, bool)))
+    # whole layer step with the predicted set
+    y.fill_(float("nan"))
+    ctx.layer_step(L, x, y)
+    torch.cuda.synchronize()
+    wptr, iptr, cptr = ctx.last_active()
+    words = torch.empty(cfg.ffn // 64, dtype=torch.int64, device="cuda")
+    pf.copy_from_device_address(words, wptr)
+    pmask = _words_to_mask(words, cfg.ffn)
+    check_active_set(pmask, O.predict(xh)["scores"], cfg.threshold, "int4 layer_step")
+    check_output(y.cpu().numpy(), O.masked_ffn(xh, pmask), "int4 layer_step")
+    y2 = torch.empty_like(y)
+    ctx.layer_step(L, x, y2)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
