@@ -155,7 +155,7 @@ void pf_plan_destroy(pf_plan *plan);
  * timed with a pair of HIP events on its own stream, up to 32768 launches.
  * pf_profile_end waits for the recorded events (the only call here that synchronises with
  * the host) and fills one entry per kernel: name (host string), launches, summed ms.
- * stats: HOST array of `capacity` >= 8 entries; *n_out receives the number filled.
+ * stats: HOST array of `capacity` >= 16 entries; *n_out receives the number filled.
  * The events are stamped by the launch itself (hipExtLaunchKernelGGL) with the kernel's
  * start and end on its stream, so launch gaps are not part of the figures. */
 typedef struct {

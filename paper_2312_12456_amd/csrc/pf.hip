@@ -17,6 +17,7 @@
 #include "k_sparse.h"
 #include "k_fused.h"
 #include "k_int4.h"
+#include "k_mfma.h"
 
 namespace {
 
@@ -27,11 +28,12 @@ constexpr int kLdsMax = 160 * 1024;     // LDS per workgroup on gfx950
 constexpr int kLdsDefault = 64 * 1024;  // what a kernel may use without opting in
 
 enum KernelId {
-    K_PRED_HIDDEN = 0, K_PRED_OUT, K_COMPACT, K_UP, K_DOWN, K_GLUE, K_OUT_UP, K_DOWN_MASK, K_NUM
+    K_PRED_HIDDEN = 0, K_PRED_OUT, K_COMPACT, K_UP, K_DOWN, K_GLUE, K_OUT_UP, K_DOWN_MASK,
+    K_UP_MFMA, K_NUM
 };
 const char *const kKernelNames[K_NUM] = {"k_pred_hidden", "k_pred_out", "k_compact", "k_up",
                                          "k_down",        "k_glue",     "k_pred_out_up",
-                                         "k_down_mask"};
+                                         "k_down_mask",   "k_up_mfma"};
 
 }  // namespace
 
@@ -41,6 +43,7 @@ struct pf_ctx {
     int num_cu = 256;
     int up_grid_cap = 2048;
     int lds_budget = kLdsDefault;  // dynamic LDS a kernel of this context may request
+    int mfma_min_batch = 4;        // FC1 goes to the matrix cores from this batch size on
     bool no_fused = true;          // PF_FUSED=1 selects the three-launch layer step (k_fused.h)
     // scratch (device)
     float *t = nullptr;              // [max_batch][max_r] predictor hidden vector
@@ -328,7 +331,22 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     int up_grid = cdiv(D.ffn, pf::kUpWaves);
     if (up_grid > ctx->up_grid_cap) up_grid = ctx->up_grid_cap;
     const bool gated = D.act == PF_ACT_REGLU;
-    for (int b0 = 0; b0 < B; b0 += tile) {
+    const bool mfma = B >= ctx->mfma_min_batch && D.d % 32 == 0;
+    if (mfma) {  // the whole batch in one launch: tokens are the N columns of the tile
+        int grid = cdiv(cdiv(D.ffn, pf::kMfmaRows), pf::kMfmaWaves);
+        if (grid > ctx->up_grid_cap) grid = ctx->up_grid_cap;
+        ProfScope ps(ctx, K_UP_MFMA);
+#define PF_UPM(ACT, FM)                                                                           \
+    PF_LAUNCH(ps, (pf::k_up_mfma<ACT, FM>), dim3(grid), dim3(pf::kMfmaThreads), extra, st, w_up,  \
+              w_gate, L->w.b_up, x, B, idx_in, count_in, mask_words, ctx->idx, ctx->count, ctx->h, \
+              D.d, D.ffn)
+        if (gated && from_mask) { PF_UPM(1, true); }
+        else if (gated) { PF_UPM(1, false); }
+        else if (from_mask) { PF_UPM(0, true); }
+        else { PF_UPM(0, false); }
+#undef PF_UPM
+    }
+    for (int b0 = 0; b0 < B && !mfma; b0 += tile) {
         const int bt = (B - b0) < tile ? (B - b0) : tile;
         const size_t lds = ((size_t)bt * kpad_of(D.d) + pf::kStageScrap) * sizeof(float) + extra;
         const float *xb = x + (size_t)b0 * D.d;
@@ -500,6 +518,10 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         if (prop.multiProcessorCount > 0) ctx->num_cu = prop.multiProcessorCount;
         ctx->up_grid_cap = 8 * ctx->num_cu;
         if (const char *v = getenv("PF_FUSED")) ctx->no_fused = atoi(v) == 0;
+        if (const char *v = getenv("PF_MFMA_MIN_B")) {
+            int c = atoi(v);
+            if (c >= 1) ctx->mfma_min_batch = c;
+        }
         if (const char *v = getenv("PF_UP_GRID")) {
             int c = atoi(v);
             if (c >= 1 && c <= 65535) ctx->up_grid_cap = c;

@@ -331,3 +331,50 @@ def test_int4_exact_mask_and_layer_step(pf, oracle, act, shape, B):
     ctx.layer_step(L, x, y2)
     torch.cuda.synchronize()
     assert torch.equal(y, y2)
+
+
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
+@pytest.mark.parametrize("d", [800, 2080])          # 25 and 65 K-steps of 32: ragged unroll tails
+@pytest.mark.parametrize("B", [4, 7, 8])
+def test_fc1_on_matrix_cores_matches_oracle_and_vector_path(pf, oracle, act, d, B, monkeypatch):
+    """From batch 4 on FC1 runs on MFMA (fp16 hi/lo split of x): same oracle bar, list slots
+    spanning several 32-row passes with a ragged last pass, and agreement with the vector-ALU
+    kernel forced through PF_MFMA_MIN_B."""
+    cfg = small_cfg(d=d, ffn=1344, r=136, rate=0.12, act=act)
+    lay = wl.make_layer(cfg, 0, seed=500 + B + act, device="cuda")
+    O = oracle_layer(cfg, wl.to_host(lay))
+    x = wl.make_inputs(cfg, 0, seed=6, batch=B, device="cuda")
+    xh = x.cpu().numpy()
+    mask = O.exact_mask(xh)
+    if mask.sum() % 32 == 0:          # keep the last 32-row pass ragged
+        mask[np.flatnonzero(mask)[-1]] = False
+    ref_idx = oracle.compact(mask)
+    assert ref_idx.size % 32 != 0 and ref_idx.size > 64
+    idx = torch.zeros(cfg.ffn, dtype=torch.int32, device="cuda")
+    idx[:ref_idx.size] = torch.from_numpy(ref_idx).cuda()
+    count = torch.tensor([ref_idx.size], dtype=torch.int32, device="cuda")
+    outs = {}
+    for name, min_b in (("mfma", "4"), ("valu", "99")):
+        monkeypatch.setenv("PF_MFMA_MIN_B", min_b)
+        ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
+        L = pf.Layer.from_workload(ctx, cfg, lay)
+        y = torch.full((B, cfg.d), float("nan"), device="cuda")
+        ctx.sparse_ffn(L, x, idx, count, y)
+        torch.cuda.synchronize()
+        check_output(y.cpu().numpy(), O.masked_ffn(xh, mask), name + " exact mask")
+        yl = torch.full((B, cfg.d), float("nan"), device="cuda")
+        ctx.layer_step(L, x, yl)
+        torch.cuda.synchronize()
+        wptr, iptr, cptr = ctx.last_active()
+        words = torch.empty(cfg.ffn // 64, dtype=torch.int64, device="cuda")
+        lidx = torch.empty(cfg.ffn, dtype=torch.int32, device="cuda")
+        cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+        pf.copy_from_device_address(words, wptr)
+        pf.copy_from_device_address(lidx, iptr)
+        pf.copy_from_device_address(cnt, cptr)
+        pmask = _words_to_mask(words, cfg.ffn)
+        assert np.array_equal(lidx.cpu().numpy()[:int(cnt.item())], oracle.compact(pmask))
+        check_output(yl.cpu().numpy(), O.masked_ffn(xh, pmask), name + " layer_step")
+        outs[name] = (y.cpu().numpy(), yl.cpu().numpy())
+    np.testing.assert_allclose(outs["mfma"][0], outs["valu"][0], atol=2e-4, rtol=0)
+    np.testing.assert_allclose(outs["mfma"][1], outs["valu"][1], atol=2e-4, rtol=0)
