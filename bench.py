@@ -140,6 +140,7 @@ def main():
         "k_down": k_mean * cfg.row_bytes,
         "k_down_mask": k_mean * cfg.row_bytes,
     }
+    alg_bytes["k_up_mfma"] = alg_bytes["k_up"]
     alg_bytes["k_pred_out_up"] = alg_bytes["k_pred_out"] + alg_bytes["k_up"]
     kernels = {}
     for name, (launches, total_ms) in stats.items():
@@ -165,7 +166,9 @@ def main():
         t_up_us = max(kernels["k_pred_out_up"]["avg_us"] - kernels["k_pred_out"]["avg_us"], 0.05)
         t_sparse_us = t_up_us + kernels["k_down_mask"]["avg_us"]
     else:
-        t_sparse_us = kernels["k_up"]["avg_us"] + kernels["k_down"]["avg_us"]
+        up_name = "k_up_mfma" if "k_up_mfma" in kernels else "k_up"
+        t_sparse_us = kernels[up_name]["avg_us"] + kernels["k_down"]["avg_us"] + \
+            kernels.get("k_combine", {"avg_us": 0.0})["avg_us"]
     touched_gbps = touched / (t_sparse_us * 1e-6) / 1e9
 
     # ---- CPU oracle on the host cores, bounded sample --------------------------------

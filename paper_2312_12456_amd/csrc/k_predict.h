@@ -13,6 +13,7 @@
 namespace pf {
 
 constexpr int kPredThreads = 256;  // 4 waves per workgroup
+constexpr int kGlueMaxParts = 4;   // FC2 may hand its output over as up to 4 partial sums
 constexpr int kPredWaves = kPredThreads / kWave;
 
 // ---------------------------------------------------------------------------------------
@@ -21,10 +22,13 @@ constexpr int kPredWaves = kPredThreads / kWave;
 // FFN output, x = (xp + yp) * sqrt(d) / ||xp + yp||_2 per token (the stack's residual +
 // scale-only RMS norm): every block stages v = xp + yp, reduces ||v||^2 itself and applies
 // the scale to its dot products; block 0 also writes x for the kernels that follow.
+// yp may arrive as ny <= 4 partial sums, ypstride floats apart (row-split FC2): they are
+// added in the fixed order 0 .. ny-1.
 template <int B, bool GLUE>
 __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__restrict__ p1,
                                                               const float *__restrict__ x,
-                                                              const float *__restrict__ yp,
+                                                              const float *__restrict__ yp, int ny,
+                                                              int ypstride,
                                                               float *__restrict__ x_new,
                                                               float *__restrict__ t, int d, int r)
 {
@@ -47,13 +51,14 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
         float ss[B];
 #pragma unroll
         for (int b = 0; b < B; ++b) ss[b] = 0.f;
-        constexpr int S = (B >= 4) ? 1 : 4 / B;  // strides whose loads are issued together
+        constexpr int S = (B >= 2) ? 1 : 2;  // strides whose loads are issued together
         constexpr int step = kPredThreads * 4;
         bool issued = false;
         const rsrc_t xr = make_rsrc(x, (uint32_t)B * (uint32_t)d * 4u);
-        const rsrc_t yr = make_rsrc(yp, (uint32_t)B * (uint32_t)d * 4u);
+        const uint32_t pbytes = (uint32_t)ypstride * 4u;  // distance between partials
+        const rsrc_t yr = make_rsrc(yp, (uint32_t)(ny - 1) * pbytes + (uint32_t)B * (uint32_t)d * 4u);
         for (int e0 = threadIdx.x * 4; e0 < kpad; e0 += step * S) {
-            float4 va[S][B], vc[S][B];
+            float4 va[S][B], vc[S][B], vp[S][B][kGlueMaxParts - 1];
 #pragma unroll
             for (int s = 0; s < S; ++s) {
                 const int e = e0 + s * step;
@@ -62,6 +67,9 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
                     const uint32_t off = e < d ? (uint32_t)(b * d + e) * 4u : kOobOffset;
                     va[s][b] = ld16_f32(xr, off);
                     vc[s][b] = ld16_f32(yr, off);
+#pragma unroll
+                    for (int p = 1; p < kGlueMaxParts; ++p)  // partial sums of FC2, in order
+                        vp[s][b][p - 1] = ld16_f32(yr, (e < d && p < ny) ? off + (uint32_t)p * pbytes : kOobOffset);
                 }
             }
             // the row's own loads queue up behind the first pass of activations
@@ -74,7 +82,13 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
                 const int e = e0 + s * step;
 #pragma unroll
                 for (int b = 0; b < B; ++b) {  // strides past the vector hold zeros: scrap slot
-                    const float4 a = va[s][b], c = vc[s][b];
+                    const float4 a = va[s][b];
+                    float4 c = vc[s][b];
+#pragma unroll
+                    for (int p = 1; p < kGlueMaxParts; ++p) {
+                        const float4 q = vp[s][b][p - 1];
+                        c = make_float4(c.x + q.x, c.y + q.y, c.z + q.z, c.w + q.w);
+                    }
                     const float4 v = make_float4(a.x + c.x, a.y + c.y, a.z + c.z, a.w + c.w);
                     ss[b] = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss[b]))));
                     *reinterpret_cast<float4 *>(xs + (e < kpad ? b * kpad + lds_slot(e) : B * kpad)) = v;

@@ -272,19 +272,151 @@ __global__ __launch_bounds__(kDownThreads) void k_down(
 }
 
 // ---------------------------------------------------------------------------------------
+// FC2, row-split form.  The vector memory path of a CU handles gathered rows at a few
+// nanoseconds per distinct 128-byte line, so k_down above -- where every workgroup walks
+// the whole list -- is bound by k lines per CU, not by HBM.  Here a workgroup owns 64
+// output columns (one full line per row: 8 lanes x 16 bytes) and only every P-th list slot
+// (slot = P * row + g for row group g), so a CU touches k * d / (64 * CUs) lines.  The P
+// partial sums of a column tile are NOT combined here: partial g goes to part[g][b][d]
+// (group 0 adds b_down) and the consumer adds the P partials in the fixed order
+// g = 0 .. P-1 -- the next layer's predictor kernel inside a stack, k_combine otherwise.
+// grid = (d / 64 tiles, P), block = 512: 64 list slots per load of the block.
+constexpr int kDown2Threads = 512;
+constexpr int kDown2Waves = kDown2Threads / kWave;
+constexpr int kDown2Cols = 64;
+constexpr int kDown2RowsPerLoad = kDown2Threads / 8;
+constexpr int kDown2MaxSplit = 4;
+
+template <int B>
+__global__ __launch_bounds__(kDown2Threads) void k_down2(
+    const __half *__restrict__ w_down, const float *__restrict__ b_down,
+    const float *__restrict__ h, const int32_t *__restrict__ idx,
+    const int32_t *__restrict__ count_p, float *__restrict__ part, int d, int ffn)
+{
+    constexpr int U = (B <= 2) ? 8 : 4;
+    __shared__ float red[kDown2Waves][B][kDown2Cols];
+    const int P = gridDim.y, g = blockIdx.y, tile = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cl = lane & 7;                      // which 16 bytes of the row's 128-byte line
+    const int rslot = wave * 8 + (lane >> 3);     // row slot of this lane inside a load
+    const int col = tile * kDown2Cols + cl * 8;
+    const bool colok = col < d;
+    const rsrc_t wd = make_rsrc(w_down, (uint32_t)ffn * (uint32_t)d * 2u);
+
+    float acc[B][8];
+#pragma unroll
+    for (int b = 0; b < B; ++b)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
+
+    int n = 0;
+    bool have_n = false;
+    for (int r0 = 0; r0 == 0 || r0 * P < n; r0 += kDown2RowsPerLoad * U) {
+        uint4 w[U];
+        float hv[U][B];
+        int iv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {  // loads that depend on the slot number only
+            const int jc = min((r0 + u * kDown2RowsPerLoad + rslot) * P + g, ffn - 1);
+            iv[u] = idx[jc];
+#pragma unroll
+            for (int b = 0; b < B; ++b) hv[u][b] = h[(size_t)b * ffn + jc];
+        }
+        if (!have_n) {
+            n = min(max(*count_p, 0), ffn);
+            have_n = true;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int jj = (r0 + u * kDown2RowsPerLoad + rslot) * P + g;
+            const bool ok = jj < n && (unsigned)iv[u] < (unsigned)ffn;
+            w[u] = ld16_stream(wd, (ok && colok) ? ((uint32_t)iv[u] * (uint32_t)d + (uint32_t)col) * 2u
+                                                 : kOobOffset);
+#pragma unroll
+            for (int b = 0; b < B; ++b) hv[u][b] = ok ? hv[u][b] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float f0 = h_lo(w[u].x), f1 = h_hi(w[u].x), f2 = h_lo(w[u].y), f3 = h_hi(w[u].y);
+            const float f4 = h_lo(w[u].z), f5 = h_hi(w[u].z), f6 = h_lo(w[u].w), f7 = h_hi(w[u].w);
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const float s = hv[u][b];
+                acc[b][0] = fmaf(s, f0, acc[b][0]);
+                acc[b][1] = fmaf(s, f1, acc[b][1]);
+                acc[b][2] = fmaf(s, f2, acc[b][2]);
+                acc[b][3] = fmaf(s, f3, acc[b][3]);
+                acc[b][4] = fmaf(s, f4, acc[b][4]);
+                acc[b][5] = fmaf(s, f5, acc[b][5]);
+                acc[b][6] = fmaf(s, f6, acc[b][6]);
+                acc[b][7] = fmaf(s, f7, acc[b][7]);
+            }
+        }
+    }
+
+    // sum the 8 row slots of the wave (lane bits 3..5), then the 8 waves through LDS
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = acc[b][e];
+            v += dpp_f32<0x128>(v);  // row_ror:8 -> lane ^ 8 within a row of 16
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            if (lane < 8) red[wave][b][cl * 8 + e] = v;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < B * kDown2Cols) {
+        const int b = threadIdx.x / kDown2Cols, c = threadIdx.x % kDown2Cols;
+        const int oc = tile * kDown2Cols + c;
+        if (oc < d) {
+            float s = (g == 0 && b_down) ? b_down[oc] : 0.f;
+#pragma unroll
+            for (int wv = 0; wv < kDown2Waves; ++wv) s += red[wv][b][c];
+            part[((size_t)g * B + b) * d + oc] = s;
+        }
+    }
+}
+
+// y[b][c] = sum of the P partials in order (for callers that need FC2's output itself).
+__global__ __launch_bounds__(256) void k_combine(const float *__restrict__ part, int P, int n,
+                                                 float *__restrict__ y)
+{
+    const int e = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (e >= n) return;
+    float4 s = *reinterpret_cast<const float4 *>(part + e);
+    for (int p = 1; p < P; ++p) {
+        const float4 v = *reinterpret_cast<const float4 *>(part + (size_t)p * n + e);
+        s.x += v.x;
+        s.y += v.y;
+        s.z += v.z;
+        s.w += v.w;
+    }
+    *reinterpret_cast<float4 *>(y + e) = s;
+}
+
+// ---------------------------------------------------------------------------------------
 // Stack glue: x_next[b] = (x[b] + y[b]) * sqrt(d) / ||x[b] + y[b]||_2.  grid = B.
 constexpr int kGlueThreads = 1024;
 
 // x_next may alias x: every element is read and written by the same thread.
+// y may come as ny partial sums [ny][B][d] (see k_down2): they are added in order.
 __global__ __launch_bounds__(kGlueThreads) void k_glue(const float *x, const float *__restrict__ y,
-                                                       float *x_next, int d)
+                                                       int ny, float *x_next, int d)
 {
     __shared__ float wsum[kGlueThreads / kWave];
     const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t pstride = (size_t)gridDim.x * d;
     const float *xb = x + (size_t)b * d, *yb = y + (size_t)b * d;
+    auto ysum = [&](int c) {
+        float t = yb[c];
+        for (int p = 1; p < ny; ++p) t += yb[p * pstride + c];
+        return t;
+    };
     float ss = 0.f;
     for (int c = threadIdx.x; c < d; c += kGlueThreads) {
-        const float v = xb[c] + yb[c];
+        const float v = xb[c] + ysum(c);
         ss = fmaf(v, v, ss);
     }
     ss = wave_sum(ss);
@@ -294,7 +426,7 @@ __global__ __launch_bounds__(kGlueThreads) void k_glue(const float *x, const flo
 #pragma unroll
     for (int k = 0; k < kGlueThreads / kWave; ++k) tot += wsum[k];
     const float scale = tot > 0.f ? sqrtf((float)d / tot) : 0.f;
-    for (int c = threadIdx.x; c < d; c += kGlueThreads) x_next[(size_t)b * d + c] = (xb[c] + yb[c]) * scale;
+    for (int c = threadIdx.x; c < d; c += kGlueThreads) x_next[(size_t)b * d + c] = (xb[c] + ysum(c)) * scale;
 }
 
 }  // namespace pf

@@ -29,11 +29,11 @@ constexpr int kLdsDefault = 64 * 1024;  // what a kernel may use without opting 
 
 enum KernelId {
     K_PRED_HIDDEN = 0, K_PRED_OUT, K_COMPACT, K_UP, K_DOWN, K_GLUE, K_OUT_UP, K_DOWN_MASK,
-    K_UP_MFMA, K_NUM
+    K_UP_MFMA, K_COMBINE, K_NUM
 };
 const char *const kKernelNames[K_NUM] = {"k_pred_hidden", "k_pred_out", "k_compact", "k_up",
                                          "k_down",        "k_glue",     "k_pred_out_up",
-                                         "k_down_mask",   "k_up_mfma"};
+                                         "k_down_mask",   "k_up_mfma",  "k_combine"};
 
 }  // namespace
 
@@ -43,6 +43,7 @@ struct pf_ctx {
     int num_cu = 256;
     int up_grid_cap = 2048;
     int lds_budget = kLdsDefault;  // dynamic LDS a kernel of this context may request
+    int down_split = 0;            // PF_DOWN_SPLIT: row groups of FC2 (0 = from the CU count)
     int mfma_min_batch = 4;        // FC1 goes to the matrix cores from this batch size on
     bool no_fused = true;          // PF_FUSED=1 selects the three-launch layer step (k_fused.h)
     // scratch (device)
@@ -51,7 +52,7 @@ struct pf_ctx {
     int32_t *idx = nullptr;          // [max_ffn]
     int32_t *count = nullptr;        // [1]
     float *h = nullptr;              // [max_batch][max_ffn] FC1 outputs of the listed neurons
-    float *ybuf = nullptr;           // [max_batch][max_d] FFN output inside pf_stack_step
+    float *ypart = nullptr;          // [4][max_batch][max_d] FC2 output as partial sums
     float *xbuf[2] = {nullptr, nullptr};  // [max_batch][max_d] layer inputs inside pf_stack_step
     hipStream_t capture_stream = nullptr;
     // per-kernel timing with HIP events (pf_profile_begin / pf_profile_end)
@@ -202,7 +203,7 @@ struct ProfScope {
 // Predictor hidden layer.  With glue_y the layer input is formed inside the kernel as
 // norm(x + glue_y) and also written to x_new.
 pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
-                        float *x_new, int B, hipStream_t st)
+                        int glue_ny, float *x_new, int B, hipStream_t st)
 {
     const pf_layer_desc &D = L->desc;
     if (!L->w.p1 || !L->w.p2) return fail(ctx, PF_EINVAL, "layer has no predictor weights");
@@ -218,12 +219,12 @@ pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const fl
         if (glue_y) {
             PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_pred_hidden<BT, true>), grid,
                                                dim3(pf::kPredThreads), lds, st, p1, x + xo,
-                                               glue_y + xo, x_new + xo, ctx->t + (size_t)b0 * D.r,
-                                               D.d, D.r));
+                                               glue_y + xo, glue_ny, B * D.d, x_new + xo,
+                                               ctx->t + (size_t)b0 * D.r, D.d, D.r));
         } else {
             PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_pred_hidden<BT, false>), grid,
                                                dim3(pf::kPredThreads), lds, st, p1, x + xo,
-                                               (const float *)nullptr, (float *)nullptr,
+                                               (const float *)nullptr, 0, 0, (float *)nullptr,
                                                ctx->t + (size_t)b0 * D.r, D.d, D.r));
         }
     }
@@ -233,9 +234,10 @@ pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const fl
 
 // Predictor: hidden layer, then output layer + ballot into mask words.
 pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
-                         float *x_new, int B, float *scores, uint64_t *mask_words, hipStream_t st)
+                         int glue_ny, float *x_new, int B, float *scores, uint64_t *mask_words,
+                         hipStream_t st)
 {
-    pf_status s = launch_hidden(ctx, L, x, glue_y, x_new, B, st);
+    pf_status s = launch_hidden(ctx, L, x, glue_y, glue_ny, x_new, B, st);
     if (s != PF_OK) return s;
     const pf_layer_desc &D = L->desc;
     const __half *p2 = static_cast<const __half *>(L->w.p2);
@@ -315,13 +317,18 @@ pf_status launch_sparse_i4(pf_ctx *ctx, const pf_layer *L, const float *x, int B
 
 // Sparse FFN.  Either an index list is given (idx_in, count_in) or mask words, from which
 // the FC1 kernel derives the list itself and leaves it in ctx->idx / ctx->count.
+// FC2's output goes to y when ny_out is null; otherwise it may be left as *ny_out partial sums
+// in ctx->ypart ([ny][B][d]) for a consumer that adds them up itself.
 pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
                         const int32_t *idx_in, const int32_t *count_in,
-                        const uint64_t *mask_words, float *y, hipStream_t st)
+                        const uint64_t *mask_words, float *y, int *ny_out, hipStream_t st)
 {
     const pf_layer_desc &D = L->desc;
-    if (D.wtype == PF_W_INT4_G128)
-        return launch_sparse_i4(ctx, L, x, B, idx_in, count_in, mask_words, y, st);
+    if (D.wtype == PF_W_INT4_G128) {
+        if (ny_out) *ny_out = 1;
+        return launch_sparse_i4(ctx, L, x, B, idx_in, count_in, mask_words,
+                                ny_out ? ctx->ypart : y, st);
+    }
     const __half *w_up = static_cast<const __half *>(L->w.w_up);
     const __half *w_gate = static_cast<const __half *>(L->w.w_gate);
     const __half *w_down = static_cast<const __half *>(L->w.w_down);
@@ -365,19 +372,24 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     }
     const int32_t *idx = from_mask ? ctx->idx : idx_in;
     const int32_t *count = from_mask ? ctx->count : count_in;
-    const int ntiles = cdiv(D.d, pf::kDownCols);
-    const dim3 grid(cdiv(ntiles, 8) * 8);
+    // row-split FC2: enough row groups per column tile to give every CU a workgroup
+    const int tiles = cdiv(D.d, pf::kDown2Cols);
+    int P = ctx->down_split > 0 ? ctx->down_split : ctx->num_cu / tiles;
+    if (P < 1) P = 1;
+    if (P > pf::kDown2MaxSplit) P = pf::kDown2MaxSplit;
+    float *part = (ny_out || P > 1) ? ctx->ypart : y;
     {
         ProfScope ps(ctx, K_DOWN);
-        if (from_mask) {
-            PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_down<BT, true>), grid, dim3(pf::kDownThreads),
-                                              0, st, w_down, L->w.b_down, ctx->h, idx, count, y,
-                                              D.d, D.ffn, ntiles));
-        } else {
-            PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_down<BT, false>), grid,
-                                              dim3(pf::kDownThreads), 0, st, w_down, L->w.b_down,
-                                              ctx->h, idx, count, y, D.d, D.ffn, ntiles));
-        }
+        PF_SWITCH_B(B, PF_LAUNCH(ps, pf::k_down2<BT>, dim3(tiles, P), dim3(pf::kDown2Threads), 0,
+                                 st, w_down, L->w.b_down, ctx->h, idx, count, part, D.d, D.ffn));
+    }
+    if (ny_out) {
+        *ny_out = P;
+    } else if (P > 1) {
+        ProfScope ps(ctx, K_COMBINE);
+        const int nel = B * D.d;
+        PF_LAUNCH(ps, pf::k_combine, dim3(cdiv(nel, 1024)), dim3(256), 0, st,
+                  (const float *)ctx->ypart, P, nel, y);
     }
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
@@ -388,7 +400,7 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
 // otherwise predictor, FC1 with fused compaction and FC2.  x_in is the layer input as the
 // later kernels see it: x itself, or x_new when the hidden kernel forms it (glue_y given).
 pf_status launch_layer(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
-                       float *x_new, int B, float *y, hipStream_t st)
+                       int glue_ny, float *x_new, int B, float *y, int *ny_out, hipStream_t st)
 {
     const pf_layer_desc &D = L->desc;
     const float *x_in = glue_y ? x_new : x;
@@ -397,11 +409,16 @@ pf_status launch_layer(pf_ctx *ctx, const pf_layer *L, const float *x, const flo
                        fused_lds + 1024 <= (size_t)ctx->lds_budget &&
                        pf::down_mask_lds_bytes(D.ffn) + 8192 <= (size_t)kLdsDefault;
     if (!fused) {
-        pf_status s = launch_predict(ctx, L, x, glue_y, x_new, B, nullptr, ctx->mask_words, st);
+        pf_status s = launch_predict(ctx, L, x, glue_y, glue_ny, x_new, B, nullptr,
+                                     ctx->mask_words, st);
         if (s != PF_OK) return s;
-        return launch_sparse(ctx, L, x_in, B, nullptr, nullptr, ctx->mask_words, y, st);
+        return launch_sparse(ctx, L, x_in, B, nullptr, nullptr, ctx->mask_words, y, ny_out, st);
     }
-    pf_status s = launch_hidden(ctx, L, x, glue_y, x_new, B, st);
+    if (ny_out) {
+        *ny_out = 1;
+        y = ctx->ypart;
+    }
+    pf_status s = launch_hidden(ctx, L, x, glue_y, glue_ny, x_new, B, st);
     if (s != PF_OK) return s;
     const __half *p2 = static_cast<const __half *>(L->w.p2);
     const __half *w_up = static_cast<const __half *>(L->w.w_up);
@@ -434,12 +451,12 @@ pf_status launch_layer(pf_ctx *ctx, const pf_layer *L, const float *x, const flo
     return PF_OK;
 }
 
-pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int d, int B, float *x_next,
-                      hipStream_t st)
+pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int ny, int d, int B,
+                      float *x_next, hipStream_t st)
 {
     {
         ProfScope ps(ctx, K_GLUE);
-        PF_LAUNCH(ps, pf::k_glue, dim3(B), dim3(pf::kGlueThreads), 0, st, x, y, x_next, d);
+        PF_LAUNCH(ps, pf::k_glue, dim3(B), dim3(pf::kGlueThreads), 0, st, x, y, ny, x_next, d);
     }
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
@@ -450,21 +467,22 @@ pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int d, int B,
 pf_status stack_enqueue(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x, int B,
                         float *x_out, hipStream_t st)
 {
+    int ny = 1;            // partial sums FC2 left in ctx->ypart
     const float *cur = x;  // input of the layer being enqueued (raw input of the previous one
                            // until the hidden kernel has formed it)
     for (int l = 0; l < n_layers; ++l) {
         const pf_layer *L = layers[l];
         pf_status s;
         if (l == 0) {
-            s = launch_layer(ctx, L, cur, nullptr, nullptr, B, ctx->ybuf, st);
+            s = launch_layer(ctx, L, cur, nullptr, 0, nullptr, B, nullptr, &ny, st);
         } else {
             float *xn = ctx->xbuf[l & 1];
-            s = launch_layer(ctx, L, cur, ctx->ybuf, xn, B, ctx->ybuf, st);
+            s = launch_layer(ctx, L, cur, ctx->ypart, ny, xn, B, nullptr, &ny, st);
             cur = xn;
         }
         if (s != PF_OK) return s;
     }
-    return launch_glue(ctx, cur, ctx->ybuf, layers[0]->desc.d, B, x_out, st);
+    return launch_glue(ctx, cur, ctx->ypart, ny, layers[0]->desc.d, B, x_out, st);
 }
 
 pf_status check_stack(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x, int B,
@@ -518,6 +536,10 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         if (prop.multiProcessorCount > 0) ctx->num_cu = prop.multiProcessorCount;
         ctx->up_grid_cap = 8 * ctx->num_cu;
         if (const char *v = getenv("PF_FUSED")) ctx->no_fused = atoi(v) == 0;
+        if (const char *v = getenv("PF_DOWN_SPLIT")) {
+            int c = atoi(v);
+            if (c >= 1 && c <= pf::kDown2MaxSplit) ctx->down_split = c;
+        }
         if (const char *v = getenv("PF_MFMA_MIN_B")) {
             int c = atoi(v);
             if (c >= 1) ctx->mfma_min_batch = c;
@@ -547,7 +569,7 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         PF_ALLOC(ctx->idx, (size_t)max_ffn * sizeof(int32_t));
         PF_ALLOC(ctx->count, 64);
         PF_ALLOC(ctx->h, (size_t)max_batch * max_ffn * sizeof(float));
-        PF_ALLOC(ctx->ybuf, (size_t)max_batch * max_d * sizeof(float));
+        PF_ALLOC(ctx->ypart, (size_t)pf::kDown2MaxSplit * max_batch * max_d * sizeof(float));
         PF_ALLOC(ctx->xbuf[0], (size_t)max_batch * max_d * sizeof(float));
         PF_ALLOC(ctx->xbuf[1], (size_t)max_batch * max_d * sizeof(float));
 #undef PF_ALLOC
@@ -574,7 +596,7 @@ void pf_ctx_destroy(pf_ctx *ctx)
     (void)hipFree(ctx->idx);
     (void)hipFree(ctx->count);
     (void)hipFree(ctx->h);
-    (void)hipFree(ctx->ybuf);
+    (void)hipFree(ctx->ypart);
     (void)hipFree(ctx->xbuf[0]);
     (void)hipFree(ctx->xbuf[1]);
     delete ctx;
@@ -633,7 +655,7 @@ pf_status pf_predict(pf_ctx *ctx, const pf_layer *layer, const float *x, int B, 
     pf_status s = check_batch(ctx, layer, x, B);
     if (s != PF_OK) return s;
     if (!mask_words) return fail(ctx, PF_EINVAL, "mask_words is null");
-    return launch_predict(ctx, layer, x, nullptr, nullptr, B, scores, mask_words,
+    return launch_predict(ctx, layer, x, nullptr, 0, nullptr, B, scores, mask_words,
                           static_cast<hipStream_t>(stream));
 }
 
@@ -659,7 +681,8 @@ pf_status pf_sparse_ffn(pf_ctx *ctx, const pf_layer *layer, const float *x, int 
     pf_status s = check_batch(ctx, layer, x, B);
     if (s != PF_OK) return s;
     if (!idx || !count || !y) return fail(ctx, PF_EINVAL, "null argument");
-    return launch_sparse(ctx, layer, x, B, idx, count, nullptr, y, static_cast<hipStream_t>(stream));
+    return launch_sparse(ctx, layer, x, B, idx, count, nullptr, y, nullptr,
+                         static_cast<hipStream_t>(stream));
 }
 
 pf_status pf_layer_step(pf_ctx *ctx, const pf_layer *layer, const float *x, int B, float *y,
@@ -669,7 +692,8 @@ pf_status pf_layer_step(pf_ctx *ctx, const pf_layer *layer, const float *x, int 
     if (s != PF_OK) return s;
     if (!y) return fail(ctx, PF_EINVAL, "y is null");
     if (!layer->w.p1) return fail(ctx, PF_EINVAL, "layer has no predictor weights");
-    return launch_layer(ctx, layer, x, nullptr, nullptr, B, y, static_cast<hipStream_t>(stream));
+    return launch_layer(ctx, layer, x, nullptr, 0, nullptr, B, y, nullptr,
+                        static_cast<hipStream_t>(stream));
 }
 
 pf_status pf_ctx_last_active(pf_ctx *ctx, const uint64_t **mask_words, const int32_t **idx,
@@ -688,7 +712,7 @@ pf_status pf_stack_glue(pf_ctx *ctx, const float *x, const float *y, int d, int 
     if (!ctx) return PF_EINVAL;
     if (!x || !y || !x_next) return fail(ctx, PF_EINVAL, "null argument");
     if (d < 1 || B < 1) return fail(ctx, PF_EINVAL, "non-positive size");
-    return launch_glue(ctx, x, y, d, B, x_next, static_cast<hipStream_t>(stream));
+    return launch_glue(ctx, x, y, 1, d, B, x_next, static_cast<hipStream_t>(stream));
 }
 
 pf_status pf_stack_step(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x, int B,
