@@ -336,4 +336,125 @@ __global__ __launch_bounds__(kDownI4Threads) void k_down_i4(
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// FC2, int4, row-split form (see k_down2): a workgroup owns 256 output columns = one full
+// 128-byte line of nibbles per row (8 lanes x 16 bytes, 32 columns per lane) and every P-th
+// list slot; partial g goes to part[g][b][d], group 0 adds b_down, the consumer adds the
+// partials in order.  grid = (d / 256, P), block = 512.
+constexpr int kDown2I4Threads = 512;
+constexpr int kDown2I4Waves = kDown2I4Threads / kWave;
+constexpr int kDown2I4Cols = 256;
+constexpr int kDown2I4RowsPerLoad = kDown2I4Threads / 8;
+
+template <int B>
+__global__ __launch_bounds__(kDown2I4Threads) void k_down2_i4(
+    const uint8_t *__restrict__ q_down, const __half *__restrict__ s_down,
+    const float *__restrict__ b_down, const float *__restrict__ h,
+    const int32_t *__restrict__ idx, const int32_t *__restrict__ count_p, float *__restrict__ part,
+    int d, int ffn)
+{
+    constexpr int U = (B <= 2) ? 4 : 2;
+    __shared__ float red[kDown2I4Waves][B][kDown2I4Cols];
+    const int P = gridDim.y, g = blockIdx.y, tile = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cl = lane & 7;                   // which 16 bytes (32 columns) of the row's line
+    const int rslot = wave * 8 + (lane >> 3);  // row slot of this lane inside a load
+    const int col = tile * kDown2I4Cols + cl * 32;
+    const bool colok = col < d;
+    const int ngroups = d / kI4Group;
+    const rsrc_t wq = make_rsrc(q_down, (uint32_t)ffn * (uint32_t)(d / 2));
+    const rsrc_t ws = make_rsrc(s_down, (uint32_t)ffn * (uint32_t)ngroups * 2u);
+
+    float acc[B][32], wsum[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+        wsum[b] = 0.f;
+#pragma unroll
+        for (int c = 0; c < 32; ++c) acc[b][c] = 0.f;
+    }
+
+    int n = 0;
+    bool have_n = false;
+    for (int r0 = 0; r0 == 0 || r0 * P < n; r0 += kDown2I4RowsPerLoad * U) {
+        int iv[U];
+        float hv[U][B];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {  // loads that depend on the slot number only
+            const int jc = min((r0 + u * kDown2I4RowsPerLoad + rslot) * P + g, ffn - 1);
+            iv[u] = idx[jc];
+#pragma unroll
+            for (int b = 0; b < B; ++b) hv[u][b] = h[(size_t)b * ffn + jc];
+        }
+        if (!have_n) {
+            n = min(max(*count_p, 0), ffn);
+            have_n = true;
+        }
+        uint4 w[U];
+        unsigned short sc[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int jj = (r0 + u * kDown2I4RowsPerLoad + rslot) * P + g;
+            const bool ok = jj < n && (unsigned)iv[u] < (unsigned)ffn && colok;
+            w[u] = ld16_stream(wq, ok ? (uint32_t)iv[u] * (uint32_t)(d / 2) + (uint32_t)col / 2u : kOobOffset);
+            sc[u] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(
+                ws, ok ? (int)(((uint32_t)iv[u] * (uint32_t)ngroups + (uint32_t)col / kI4Group) * 2u)
+                       : (int)kOobOffset, 0, 0);
+#pragma unroll
+            for (int b = 0; b < B; ++b) hv[u][b] = ok ? hv[u][b] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float scale = half_bits_to_float(sc[u]);
+            const uint32_t dws[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+            float hs[B];
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                hs[b] = hv[u][b] * scale;
+                wsum[b] += hs[b];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float f[8];
+                nibbles8(dws[k], f);
+#pragma unroll
+                for (int b = 0; b < B; ++b)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[b][8 * k + e] = fmaf(hs[b], f[e], acc[b][8 * k + e]);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+#pragma unroll
+        for (int c = 0; c < 32; ++c) acc[b][c] = fmaf(-8.f, wsum[b], acc[b][c]);
+        // halving butterfly over the 8 row slots of the wave (lane bits 5, 4, 3): a lane ends
+        // with 4 of its 32 columns, summed over the 8 rows
+#pragma unroll
+        for (int D = 32, nv = 16; D >= 8; D >>= 1, nv >>= 1) {
+            const bool upper = (lane & D) != 0;
+#pragma unroll
+            for (int k = 0; k < nv; ++k) {
+                const float send = upper ? acc[b][k] : acc[b][k + nv];
+                const float keep = upper ? acc[b][k + nv] : acc[b][k];
+                acc[b][k] = keep + __shfl_xor(send, D, 64);
+            }
+        }
+        const int sub = ((lane >> 5) & 1) * 16 + ((lane >> 4) & 1) * 8 + ((lane >> 3) & 1) * 4;
+        *reinterpret_cast<float4 *>(&red[wave][b][cl * 32 + sub]) =
+            make_float4(acc[b][0], acc[b][1], acc[b][2], acc[b][3]);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < B * kDown2I4Cols; e += kDown2I4Threads) {
+        const int b = e / kDown2I4Cols, c = e % kDown2I4Cols;
+        const int oc = tile * kDown2I4Cols + c;
+        if (oc < d) {
+            float s = (g == 0 && b_down) ? b_down[oc] : 0.f;
+#pragma unroll
+            for (int wv = 0; wv < kDown2I4Waves; ++wv) s += red[wv][b][c];
+            part[((size_t)g * B + b) * d + oc] = s;
+        }
+    }
+}
+
 }  // namespace pf

@@ -19,18 +19,17 @@ namespace pf {
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4v_t __attribute__((ext_vector_type(4)));
 
-constexpr int kMfmaThreads = 256;
-constexpr int kMfmaWaves = kMfmaThreads / kWave;
-constexpr int kMfmaRT = 2;                    // 16-row tiles per wave pass
-constexpr int kMfmaRows = 16 * kMfmaRT;       // list slots per wave pass
-constexpr int kMfmaKU = 4;                    // K steps (of 32) whose loads are in flight together
+constexpr int kMfmaThreads = 512;
+constexpr int kMfmaWaves = kMfmaThreads / kWave;  // the waves of a block split K between them
+constexpr int kMfmaRows = 16;                     // list slots per block pass: one MFMA tile
+constexpr int kMfmaKU = 8;                        // K steps (of 32) whose loads are in flight together
 
 union Half8Bits {
     uint4 u;
     half8_t h;
 };
 
-// Split 8 fp32 values into fp16 hi (truncated) and fp16 lo (residual) vectors.
+// Split 8 fp32 values into fp16 hi (rounded) and fp16 lo (residual) vectors.
 __device__ __forceinline__ void split_hi_lo(const float4 &a, const float4 &b, half8_t &hi, half8_t &lo)
 {
     const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
@@ -42,7 +41,10 @@ __device__ __forceinline__ void split_hi_lo(const float4 &a, const float4 &b, ha
     }
 }
 
-// grid = any; waves stride over passes of 32 list slots.  d % 32 == 0, B <= 16.
+// grid = any; blocks stride over passes of 16 list slots; the 8 waves of a block each take
+// an eighth of the K steps of the same 16 rows (so that a pass has 8 x 16 rows x 512 bytes
+// in flight instead of one wave walking d alone) and their C tiles are added in LDS in
+// wave order.  d % 32 == 0, B <= 16.
 template <int ACT, bool FROM_MASK>
 __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
@@ -53,8 +55,10 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
 {
     extern __shared__ uint64_t dyn_lds64[];
     __shared__ uint32_t wave_tot[kMfmaWaves];
+    __shared__ float ctile[kMfmaWaves][2][256];  // per wave: C of up, C of gate (16 x 16 each)
+    __shared__ int irow[16];
     constexpr bool GATED = (ACT == 1);
-    constexpr int RT = kMfmaRT, KU = kMfmaKU;
+    constexpr int KU = kMfmaKU;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row16 = lane & 15, kg = lane >> 4;
     const int nwords = ffn / 64;
@@ -75,84 +79,79 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     const rsrc_t xr = make_rsrc(x, (uint32_t)B * (uint32_t)d * 4u);
     const uint32_t xoff = row16 < B ? ((uint32_t)row16 * (uint32_t)d + (uint32_t)kg * 8u) * 4u : kOobOffset;
     const int nsteps = d / 32;
+    const int per_wave = (nsteps + kMfmaWaves - 1) / kMfmaWaves;
+    const int s_begin = wave * per_wave, s_end = min(nsteps, s_begin + per_wave);
     const int npass = (n + kMfmaRows - 1) / kMfmaRows;
 
-    for (int pass = blockIdx.x * kMfmaWaves + wave; pass < npass; pass += gridDim.x * kMfmaWaves) {
-        // the A-operand row of this lane in each tile: list slot -> neuron id
-        int jr[RT], ir[RT];
-#pragma unroll
-        for (int r = 0; r < RT; ++r) jr[r] = pass * kMfmaRows + r * 16 + row16;
+    for (int pass = blockIdx.x; pass < npass; pass += gridDim.x) {
+        // the A-operand row of this lane: list slot -> neuron id
+        const int jr[1] = {pass * kMfmaRows + row16};
+        int ir[1];
         if (FROM_MASK) {
-            select_set_bits_lane<RT>(words_lds, pre_lds, nwords, top_step, n, jr, ir);
+            select_set_bits_lane<1>(words_lds, pre_lds, nwords, top_step, n, jr, ir);
         } else {
-#pragma unroll
-            for (int r = 0; r < RT; ++r) {
-                ir[r] = jr[r] < n ? idx_in[jr[r]] : -1;
-                if ((unsigned)ir[r] >= (unsigned)ffn) ir[r] = -1;
-            }
+            ir[0] = jr[0] < n ? idx_in[jr[0]] : -1;
+            if ((unsigned)ir[0] >= (unsigned)ffn) ir[0] = -1;
         }
-        uint32_t aoff[RT];
-#pragma unroll
-        for (int r = 0; r < RT; ++r) {
-            aoff[r] = ir[r] >= 0 ? ((uint32_t)ir[r] * (uint32_t)d + (uint32_t)kg * 8u) * 2u : kOobOffset;
-            if (FROM_MASK && kg == 0 && ir[r] >= 0) idx_out[jr[r]] = ir[r];
+        const uint32_t aoff = ir[0] >= 0 ? ((uint32_t)ir[0] * (uint32_t)d + (uint32_t)kg * 8u) * 2u : kOobOffset;
+        if (wave == 0 && kg == 0) {
+            irow[row16] = ir[0];
+            if (FROM_MASK && ir[0] >= 0) idx_out[jr[0]] = ir[0];
         }
 
-        float4v_t cu[RT], cg[RT];
-#pragma unroll
-        for (int r = 0; r < RT; ++r) {
-            cu[r] = (float4v_t){0.f, 0.f, 0.f, 0.f};
-            cg[r] = (float4v_t){0.f, 0.f, 0.f, 0.f};
-        }
-        for (int s0 = 0; s0 < nsteps; s0 += KU) {
-            Half8Bits au[KU][RT], ag[KU][RT];
+        float4v_t cu = {0.f, 0.f, 0.f, 0.f}, cg = {0.f, 0.f, 0.f, 0.f};
+        for (int s0 = s_begin; s0 < s_end; s0 += KU) {
+            Half8Bits au[KU], ag[KU];
             float4 xa[KU], xb[KU];
 #pragma unroll
             for (int u = 0; u < KU; ++u) {
-                const bool live = s0 + u < nsteps;
+                const bool live = s0 + u < s_end;
                 const uint32_t kb = (uint32_t)(s0 + u) * 32u;  // element offset of this K step
+                const uint32_t o = live && aoff != kOobOffset ? aoff + kb * 2u : kOobOffset;
+                au[u].u = ld16_stream(wu, o);
+                if (GATED) ag[u].u = ld16_stream(wg, o);
+            }
+#pragma unroll
+            for (int u = 0; u < KU; ++u) {
+                const bool live = s0 + u < s_end;
+                const uint32_t kb = (uint32_t)(s0 + u) * 32u;
                 xa[u] = ld16_f32(xr, live && xoff != kOobOffset ? xoff + kb * 4u : kOobOffset);
                 xb[u] = ld16_f32(xr, live && xoff != kOobOffset ? xoff + kb * 4u + 16u : kOobOffset);
-#pragma unroll
-                for (int r = 0; r < RT; ++r) {
-                    const uint32_t o = live && aoff[r] != kOobOffset ? aoff[r] + kb * 2u : kOobOffset;
-                    au[u][r].u = ld16_stream(wu, o);
-                    if (GATED) ag[u][r].u = ld16_stream(wg, o);
-                }
             }
 #pragma unroll
             for (int u = 0; u < KU; ++u) {
                 half8_t hi, lo;
                 split_hi_lo(xa[u], xb[u], hi, lo);
-#pragma unroll
-                for (int r = 0; r < RT; ++r) {
-                    cu[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(au[u][r].h, hi, cu[r], 0, 0, 0);
-                    cu[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(au[u][r].h, lo, cu[r], 0, 0, 0);
-                    if (GATED) {
-                        cg[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ag[u][r].h, hi, cg[r], 0, 0, 0);
-                        cg[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ag[u][r].h, lo, cg[r], 0, 0, 0);
-                    }
+                cu = __builtin_amdgcn_mfma_f32_16x16x32_f16(au[u].h, hi, cu, 0, 0, 0);
+                cu = __builtin_amdgcn_mfma_f32_16x16x32_f16(au[u].h, lo, cu, 0, 0, 0);
+                if (GATED) {
+                    cg = __builtin_amdgcn_mfma_f32_16x16x32_f16(ag[u].h, hi, cg, 0, 0, 0);
+                    cg = __builtin_amdgcn_mfma_f32_16x16x32_f16(ag[u].h, lo, cg, 0, 0, 0);
                 }
             }
         }
-        // C[row 4*kg + e][col row16]: the token is this lane's column, the neuron comes from
-        // the lane that owned that A row
+        // this lane holds C[row 4*kg + e][col row16] of its K slice
 #pragma unroll
-        for (int r = 0; r < RT; ++r) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int row = kg * 4 + e;
-                const int i = __shfl(ir[r], row, 64);
-                const int j = pass * kMfmaRows + r * 16 + row;
-                const float bias = (b_up != nullptr && i >= 0) ? b_up[i] : 0.f;
-                float v;
-                if (GATED)
-                    v = fmaxf(cg[r][e] + bias, 0.f) * cu[r][e];
-                else
-                    v = fmaxf(cu[r][e] + bias, 0.f);
-                if (row16 < B && j < n) h[(size_t)row16 * ffn + j] = i >= 0 ? v : 0.f;
-            }
+        for (int e = 0; e < 4; ++e) {
+            ctile[wave][0][(kg * 4 + e) * 16 + row16] = cu[e];
+            if (GATED) ctile[wave][1][(kg * 4 + e) * 16 + row16] = cg[e];
         }
+        __syncthreads();
+        if (threadIdx.x < 256) {
+            const int row = threadIdx.x >> 4, colb = threadIdx.x & 15;
+            float su = 0.f, sg = 0.f;
+#pragma unroll
+            for (int wv = 0; wv < kMfmaWaves; ++wv) {
+                su += ctile[wv][0][threadIdx.x];
+                if (GATED) sg += ctile[wv][1][threadIdx.x];
+            }
+            const int i = irow[row];
+            const int j = pass * kMfmaRows + row;
+            const float bias = (b_up != nullptr && i >= 0) ? b_up[i] : 0.f;
+            const float v = GATED ? fmaxf(sg + bias, 0.f) * su : fmaxf(su + bias, 0.f);
+            if (colb < B && j < n) h[(size_t)colb * ffn + j] = i >= 0 ? v : 0.f;
+        }
+        __syncthreads();
     }
 }
 

@@ -122,11 +122,16 @@ inline int batch_tile(const pf_ctx *ctx, int k, int B, size_t extra)
         default: { constexpr int BT = 8; __VA_ARGS__; } break;               \
     }
 
+// Opt a kernel in to the full 160 KB of LDS: dynamic limit = 160 KB minus its static LDS.
 template <typename K>
 hipError_t allow_lds(K kernel)
 {
+    hipFuncAttributes attr;
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(kernel));
+    if (e != hipSuccess) return e;
     return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsMax);
+                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                               kLdsMax - (int)attr.sharedSizeBytes);
 }
 
 template <int B>
@@ -259,7 +264,7 @@ inline int kpad_i4(int k) { return cdiv(k, pf::kI4Chunk) * pf::kI4Chunk; }
 // Sparse FFN over int4 weights (same launch structure as the fp16 one below).
 pf_status launch_sparse_i4(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
                            const int32_t *idx_in, const int32_t *count_in,
-                           const uint64_t *mask_words, float *y, hipStream_t st)
+                           const uint64_t *mask_words, float *y, int *ny_out, hipStream_t st)
 {
     const pf_layer_desc &D = L->desc;
     const uint8_t *q_up = static_cast<const uint8_t *>(L->w.w_up);
@@ -297,19 +302,24 @@ pf_status launch_sparse_i4(pf_ctx *ctx, const pf_layer *L, const float *x, int B
     }
     const int32_t *idx = from_mask ? ctx->idx : idx_in;
     const int32_t *count = from_mask ? ctx->count : count_in;
-    const int ntiles = cdiv(D.d, pf::kDownI4Cols);
-    const dim3 grid(cdiv(ntiles, 8) * 8);
+    const int tiles = cdiv(D.d, pf::kDown2I4Cols);
+    int P = ctx->down_split > 0 ? ctx->down_split : ctx->num_cu / tiles;
+    if (P < 1) P = 1;
+    if (P > pf::kDown2MaxSplit) P = pf::kDown2MaxSplit;
+    float *part = (ny_out || P > 1) ? ctx->ypart : y;
     {
         ProfScope ps(ctx, K_DOWN);
-        if (from_mask) {
-            PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_down_i4<BT, true>), grid, dim3(pf::kDownI4Threads),
-                                     0, st, q_down, s_down, L->w.b_down, ctx->h, idx, count, y,
-                                     D.d, D.ffn, ntiles));
-        } else {
-            PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_down_i4<BT, false>), grid,
-                                     dim3(pf::kDownI4Threads), 0, st, q_down, s_down, L->w.b_down,
-                                     ctx->h, idx, count, y, D.d, D.ffn, ntiles));
-        }
+        PF_SWITCH_B(B, PF_LAUNCH(ps, pf::k_down2_i4<BT>, dim3(tiles, P), dim3(pf::kDown2I4Threads),
+                                 0, st, q_down, s_down, L->w.b_down, ctx->h, idx, count, part, D.d,
+                                 D.ffn));
+    }
+    if (ny_out) {
+        *ny_out = P;
+    } else if (P > 1) {
+        ProfScope ps(ctx, K_COMBINE);
+        const int nel = B * D.d;
+        PF_LAUNCH(ps, pf::k_combine, dim3(cdiv(nel, 1024)), dim3(256), 0, st,
+                  (const float *)ctx->ypart, P, nel, y);
     }
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
@@ -324,11 +334,8 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
                         const uint64_t *mask_words, float *y, int *ny_out, hipStream_t st)
 {
     const pf_layer_desc &D = L->desc;
-    if (D.wtype == PF_W_INT4_G128) {
-        if (ny_out) *ny_out = 1;
-        return launch_sparse_i4(ctx, L, x, B, idx_in, count_in, mask_words,
-                                ny_out ? ctx->ypart : y, st);
-    }
+    if (D.wtype == PF_W_INT4_G128)
+        return launch_sparse_i4(ctx, L, x, B, idx_in, count_in, mask_words, y, ny_out, st);
     const __half *w_up = static_cast<const __half *>(L->w.w_up);
     const __half *w_gate = static_cast<const __half *>(L->w.w_gate);
     const __half *w_down = static_cast<const __half *>(L->w.w_down);
@@ -340,7 +347,7 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     const bool gated = D.act == PF_ACT_REGLU;
     const bool mfma = B >= ctx->mfma_min_batch && D.d % 32 == 0;
     if (mfma) {  // the whole batch in one launch: tokens are the N columns of the tile
-        int grid = cdiv(cdiv(D.ffn, pf::kMfmaRows), pf::kMfmaWaves);
+        int grid = cdiv(D.ffn, pf::kMfmaRows);
         if (grid > ctx->up_grid_cap) grid = ctx->up_grid_cap;
         ProfScope ps(ctx, K_UP_MFMA);
 #define PF_UPM(ACT, FM)                                                                           \
@@ -552,7 +559,7 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         if (prop.sharedMemPerBlock >= (size_t)kLdsMax ||
             prop.maxSharedMemoryPerMultiProcessor >= (size_t)kLdsMax) {
             if (allow_lds_all() == hipSuccess)
-                ctx->lds_budget = kLdsMax;
+                ctx->lds_budget = kLdsMax - 4096;  // room for the kernels' small static LDS
             else
                 (void)hipGetLastError();
         }
