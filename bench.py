@@ -118,14 +118,10 @@ def main():
     xa = torch.empty((B, cfg.d), device=dev)
     cnt = torch.empty(1, dtype=torch.int32, device=dev)
     _, _, count_ptr = ctx.last_active()
-    words = torch.empty(cfg.ffn // 64, dtype=torch.int64, device=dev)
     ctx.profile_begin()
     for t in range(P):
         xa.copy_(x_all[t])
         for l, L in enumerate(layers):
-            if t == 0:
-                # the predictor on its own, to split the fused output-layer + FC1 kernel's time
-                ctx.predict(L, xa, None, words)
             ctx.layer_step(L, xa, y)
             ctx.stack_glue(xa, y, xa)
             pf.copy_from_device_address(cnt, count_ptr)
@@ -138,10 +134,8 @@ def main():
         "k_pred_out": 2.0 * cfg.ffn * cfg.r + (0 if args.no_pred_bias else 4.0 * cfg.ffn),
         "k_up": k_mean * (nm - 1) * cfg.row_bytes,
         "k_down": k_mean * cfg.row_bytes,
-        "k_down_mask": k_mean * cfg.row_bytes,
     }
     alg_bytes["k_up_mfma"] = alg_bytes["k_up"]
-    alg_bytes["k_pred_out_up"] = alg_bytes["k_pred_out"] + alg_bytes["k_up"]
     kernels = {}
     for name, (launches, total_ms) in stats.items():
         if launches == 0:
@@ -160,15 +154,9 @@ def main():
         "alg_bytes_per_launch": dk["alg_bytes"], "avg_us": dk["avg_us"],
     }
     touched = k_mean * nm * cfg.row_bytes
-    if "k_pred_out_up" in kernels:
-        # FC1 shares a launch with the predictor's output layer: its share of that launch is
-        # the launch's time minus the output layer timed on its own
-        t_up_us = max(kernels["k_pred_out_up"]["avg_us"] - kernels["k_pred_out"]["avg_us"], 0.05)
-        t_sparse_us = t_up_us + kernels["k_down_mask"]["avg_us"]
-    else:
-        up_name = "k_up_mfma" if "k_up_mfma" in kernels else "k_up"
-        t_sparse_us = kernels[up_name]["avg_us"] + kernels["k_down"]["avg_us"] + \
-            kernels.get("k_combine", {"avg_us": 0.0})["avg_us"]
+    up_name = "k_up_mfma" if "k_up_mfma" in kernels else "k_up"
+    t_sparse_us = kernels[up_name]["avg_us"] + kernels["k_down"]["avg_us"] + \
+        kernels.get("k_combine", {"avg_us": 0.0})["avg_us"]
     touched_gbps = touched / (t_sparse_us * 1e-6) / 1e9
 
     # ---- CPU oracle on the host cores, bounded sample --------------------------------

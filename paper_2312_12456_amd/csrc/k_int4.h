@@ -208,139 +208,12 @@ __global__ __launch_bounds__(kUpI4Threads) void k_up_i4(
 }
 
 // ---------------------------------------------------------------------------------------
-// FC2 over listed neurons, int4 weights.  A workgroup owns 32 output columns = one 16-byte
-// run of nibbles per row; every lane takes a different row (512 rows per load of the block).
-// The 8 workgroups that share a 128-byte line have consecutive tile numbers and run on the
-// same XCD.  The lane's 32 accumulators are summed over the 64 rows of the wave by a
-// halving butterfly (31 exchanges instead of 32 full reductions), then over waves in LDS.
-constexpr int kDownI4Threads = 512;
-constexpr int kDownI4Waves = kDownI4Threads / kWave;
-constexpr int kDownI4Cols = 32;
-
-template <int B, bool SPEC>
-__global__ __launch_bounds__(kDownI4Threads) void k_down_i4(
-    const uint8_t *__restrict__ q_down, const __half *__restrict__ s_down,
-    const float *__restrict__ b_down, const float *__restrict__ h,
-    const int32_t *__restrict__ idx, const int32_t *__restrict__ count_p, float *__restrict__ y, int d,
-    int ffn, int ntiles)
-{
-    constexpr int U = (B <= 2) ? 4 : 2;
-    constexpr int STEP = kDownI4Threads * U;
-    __shared__ float red[kDownI4Waves][B][kDownI4Cols];
-    const int per_xcd = (ntiles + 7) >> 3;
-    const int tile = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
-    if (tile >= ntiles) return;  // uniform over the block
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int ngroups = d / kI4Group;
-    const rsrc_t wq = make_rsrc(q_down, (uint32_t)ffn * (uint32_t)(d / 2));
-    const rsrc_t ws = make_rsrc(s_down, (uint32_t)ffn * (uint32_t)ngroups * 2u);
-    const uint32_t col_byte = (uint32_t)tile * 16u;     // 32 columns = 16 bytes into the row
-    const uint32_t group = (uint32_t)tile / 4u;         // 128 columns per scale
-
-    float acc[B][32], wsum[B];
-#pragma unroll
-    for (int b = 0; b < B; ++b) {
-        wsum[b] = 0.f;
-#pragma unroll
-        for (int c = 0; c < 32; ++c) acc[b][c] = 0.f;
-    }
-
-    int n = 0;
-    bool have_n = false;
-    for (int j0 = 0; j0 == 0 || j0 < n; j0 += STEP) {
-        int iv[U];
-        float hv[U][B];
-        if (SPEC) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int jc = min(j0 + u * kDownI4Threads + (int)threadIdx.x, ffn - 1);
-                iv[u] = idx[jc];
-#pragma unroll
-                for (int b = 0; b < B; ++b) hv[u][b] = h[(size_t)b * ffn + jc];
-            }
-        }
-        if (!have_n) {
-            n = min(max(*count_p, 0), ffn);
-            have_n = true;
-        }
-        uint4 w[U];
-        unsigned short sc[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int jj = j0 + u * kDownI4Threads + (int)threadIdx.x;
-            bool ok = jj < n;
-            if (!SPEC) iv[u] = ok ? idx[jj] : 0;
-            ok = ok && (unsigned)iv[u] < (unsigned)ffn;
-            w[u] = ld16_stream(wq, ok ? (uint32_t)iv[u] * (uint32_t)(d / 2) + col_byte : kOobOffset);
-            sc[u] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(
-                ws, ok ? (int)(((uint32_t)iv[u] * (uint32_t)ngroups + group) * 2u) : (int)kOobOffset, 0, 0);
-#pragma unroll
-            for (int b = 0; b < B; ++b) {
-                if (SPEC)
-                    hv[u][b] = ok ? hv[u][b] : 0.f;
-                else
-                    hv[u][b] = ok ? h[(size_t)b * ffn + jj] : 0.f;
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float scale = half_bits_to_float(sc[u]);
-            const uint32_t dws[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
-            float hs[B];
-#pragma unroll
-            for (int b = 0; b < B; ++b) {
-                hs[b] = hv[u][b] * scale;
-                wsum[b] += hs[b];
-            }
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                float f[8];
-                nibbles8(dws[k], f);
-#pragma unroll
-                for (int b = 0; b < B; ++b)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[b][8 * k + e] = fmaf(hs[b], f[e], acc[b][8 * k + e]);
-            }
-        }
-    }
-
-    // y += h * scale * (u - 8): take the -8 off once, then sum the 64 rows of the wave
-#pragma unroll
-    for (int b = 0; b < B; ++b) {
-#pragma unroll
-        for (int c = 0; c < 32; ++c) acc[b][c] = fmaf(-8.f, wsum[b], acc[b][c]);
-        // halving butterfly: after the step with distance D a lane keeps half of its values
-#pragma unroll
-        for (int D = 32, nv = 16; D >= 2; D >>= 1, nv >>= 1) {
-            const bool upper = (lane & D) != 0;
-#pragma unroll
-            for (int k = 0; k < nv; ++k) {
-                const float send = upper ? acc[b][k] : acc[b][k + nv];
-                const float keep = upper ? acc[b][k + nv] : acc[b][k];
-                acc[b][k] = keep + __shfl_xor(send, D, 64);
-            }
-        }
-        const float total = acc[b][0] + __shfl_xor(acc[b][0], 1, 64);
-        if ((lane & 1) == 0) red[wave][b][lane >> 1] = total;  // lane l holds column l >> 1
-    }
-    __syncthreads();
-    if (threadIdx.x < B * kDownI4Cols) {
-        const int b = threadIdx.x / kDownI4Cols, c = threadIdx.x % kDownI4Cols;
-        const int oc = tile * kDownI4Cols + c;
-        if (oc < d) {
-            float s = b_down ? b_down[oc] : 0.f;
-#pragma unroll
-            for (int wv = 0; wv < kDownI4Waves; ++wv) s += red[wv][b][c];
-            y[(size_t)b * d + oc] = s;
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------
-// FC2, int4, row-split form (see k_down2): a workgroup owns 256 output columns = one full
-// 128-byte line of nibbles per row (8 lanes x 16 bytes, 32 columns per lane) and every P-th
-// list slot; partial g goes to part[g][b][d], group 0 adds b_down, the consumer adds the
-// partials in order.  grid = (d / 256, P), block = 512.
+// FC2 over listed neurons, int4 weights, row-split like k_down2: a workgroup owns 256 output
+// columns = one full 128-byte line of nibbles per row (8 lanes x 16 bytes, 32 columns per
+// lane) and every P-th list slot; partial g goes to part[g][b][d], group 0 adds b_down, the
+// consumer adds the partials in order.  A lane's 32 accumulators are summed over the 8 row
+// slots of its wave by a halving butterfly (a lane gives away half of its values at every
+// exchange), then over waves in LDS.  grid = (d / 256, P), block = 512.
 constexpr int kDown2I4Threads = 512;
 constexpr int kDown2I4Waves = kDown2I4Threads / kWave;
 constexpr int kDown2I4Cols = 256;

@@ -12,7 +12,6 @@
 #pragma once
 #include "dev_util.h"
 #include "k_predict.h"
-#include "k_fused.h"
 
 namespace pf {
 

@@ -296,6 +296,49 @@ __device__ __forceinline__ int select_set_bit(const uint64_t *words_lds, const u
     return w * 64 + (int)__builtin_ctzll(hit);
 }
 
+// Neuron ids of U list slots per lane (slot j[u], or -1 when j[u] >= total): binary search of
+// the prefix for the word, then of the word for the bit.  The U searches advance in
+// lockstep so that their LDS reads overlap instead of queueing one behind the other.
+template <int U>
+__device__ __forceinline__ void select_set_bits_lane(const uint64_t *words_lds,
+                                                     const uint32_t *pre_lds, int nwords,
+                                                     int top_step, int total, const int (&j)[U],
+                                                     int (&out)[U])
+{
+    int lo[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) lo[u] = 0;
+    for (int step = top_step; step >= 1; step >>= 1) {
+        uint32_t p[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) p[u] = pre_lds[min(lo[u] + step, nwords)];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (lo[u] + step < nwords && p[u] <= (uint32_t)j[u]) lo[u] += step;
+    }
+    uint64_t w[U];
+    uint32_t rank[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        w[u] = words_lds[lo[u]];
+        rank[u] = (uint32_t)j[u] - pre_lds[lo[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        int pos = 0;
+#pragma unroll
+        for (int width = 32; width >= 1; width >>= 1) {
+            const uint32_t c = (uint32_t)__popcll(w[u] & ((1ull << width) - 1ull));
+            if (rank[u] >= c) {  // the bit lies in the upper half
+                rank[u] -= c;
+                w[u] >>= width;
+                pos += width;
+            }
+        }
+        out[u] = j[u] < total ? lo[u] * 64 + pos : -1;
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // Stand-alone compaction of mask words into an ascending index list, by one workgroup.
 // Per pass of NT words: popcount prefix as above, then one wave per word; lane l owns

@@ -15,7 +15,6 @@
 
 #include "k_predict.h"
 #include "k_sparse.h"
-#include "k_fused.h"
 #include "k_int4.h"
 #include "k_mfma.h"
 
@@ -28,12 +27,10 @@ constexpr int kLdsMax = 160 * 1024;     // LDS per workgroup on gfx950
 constexpr int kLdsDefault = 64 * 1024;  // what a kernel may use without opting in
 
 enum KernelId {
-    K_PRED_HIDDEN = 0, K_PRED_OUT, K_COMPACT, K_UP, K_DOWN, K_GLUE, K_OUT_UP, K_DOWN_MASK,
-    K_UP_MFMA, K_COMBINE, K_NUM
+    K_PRED_HIDDEN = 0, K_PRED_OUT, K_COMPACT, K_UP, K_DOWN, K_GLUE, K_UP_MFMA, K_COMBINE, K_NUM
 };
 const char *const kKernelNames[K_NUM] = {"k_pred_hidden", "k_pred_out", "k_compact", "k_up",
-                                         "k_down",        "k_glue",     "k_pred_out_up",
-                                         "k_down_mask",   "k_up_mfma",  "k_combine"};
+                                         "k_down",        "k_glue",     "k_up_mfma",  "k_combine"};
 
 }  // namespace
 
@@ -45,7 +42,6 @@ struct pf_ctx {
     int lds_budget = kLdsDefault;  // dynamic LDS a kernel of this context may request
     int down_split = 0;            // PF_DOWN_SPLIT: row groups of FC2 (0 = from the CU count)
     int mfma_min_batch = 4;        // FC1 goes to the matrix cores from this batch size on
-    bool no_fused = true;          // PF_FUSED=1 selects the three-launch layer step (k_fused.h)
     // scratch (device)
     float *t = nullptr;              // [max_batch][max_r] predictor hidden vector
     uint64_t *mask_words = nullptr;  // [max_ffn / 64]
@@ -143,8 +139,6 @@ hipError_t allow_lds_for_batch()
     if (e == hipSuccess) e = allow_lds(pf::k_up<B, 1, false>);
     if (e == hipSuccess) e = allow_lds(pf::k_up<B, 0, true>);
     if (e == hipSuccess) e = allow_lds(pf::k_up<B, 1, true>);
-    if (e == hipSuccess) e = allow_lds(pf::k_pred_out_up<B, 0>);
-    if (e == hipSuccess) e = allow_lds(pf::k_pred_out_up<B, 1>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_i4<B, 0, false>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_i4<B, 1, false>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_i4<B, 0, true>);
@@ -402,60 +396,16 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     return PF_OK;
 }
 
-// Whole layer step.  Three launches when the fused kernel's LDS image fits (hidden layer;
-// output layer + FC1 of each block's own active neurons; FC2 with in-kernel compaction),
-// otherwise predictor, FC1 with fused compaction and FC2.  x_in is the layer input as the
-// later kernels see it: x itself, or x_new when the hidden kernel forms it (glue_y given).
+// Whole layer step: predictor (two launches), FC1 with fused compaction, FC2.  x_in is the
+// layer input as the later kernels see it: x itself, or x_new when the hidden kernel forms
+// it (glue_y given).
 pf_status launch_layer(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
                        int glue_ny, float *x_new, int B, float *y, int *ny_out, hipStream_t st)
 {
-    const pf_layer_desc &D = L->desc;
     const float *x_in = glue_y ? x_new : x;
-    const size_t fused_lds = pf::out_up_lds_bytes(B, D.r, D.d);
-    const bool fused = !ctx->no_fused && D.wtype == PF_W_FP16 &&
-                       fused_lds + 1024 <= (size_t)ctx->lds_budget &&
-                       pf::down_mask_lds_bytes(D.ffn) + 8192 <= (size_t)kLdsDefault;
-    if (!fused) {
-        pf_status s = launch_predict(ctx, L, x, glue_y, glue_ny, x_new, B, nullptr,
-                                     ctx->mask_words, st);
-        if (s != PF_OK) return s;
-        return launch_sparse(ctx, L, x_in, B, nullptr, nullptr, ctx->mask_words, y, ny_out, st);
-    }
-    if (ny_out) {
-        *ny_out = 1;
-        y = ctx->ypart;
-    }
-    pf_status s = launch_hidden(ctx, L, x, glue_y, glue_ny, x_new, B, st);
+    pf_status s = launch_predict(ctx, L, x, glue_y, glue_ny, x_new, B, nullptr, ctx->mask_words, st);
     if (s != PF_OK) return s;
-    const __half *p2 = static_cast<const __half *>(L->w.p2);
-    const __half *w_up = static_cast<const __half *>(L->w.w_up);
-    const __half *w_gate = static_cast<const __half *>(L->w.w_gate);
-    const __half *w_down = static_cast<const __half *>(L->w.w_down);
-    {
-        ProfScope ps(ctx, K_OUT_UP);
-        const dim3 grid(D.ffn / 64);
-        if (D.act == PF_ACT_REGLU) {
-            PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_pred_out_up<BT, 1>), grid, dim3(pf::kOutUpThreads),
-                                     fused_lds, st, p2, L->w.p_bias, ctx->t, w_up, w_gate,
-                                     L->w.b_up, x_in, D.r, D.d, D.ffn, L->thr_logit,
-                                     ctx->mask_words, ctx->h));
-        } else {
-            PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_pred_out_up<BT, 0>), grid, dim3(pf::kOutUpThreads),
-                                     fused_lds, st, p2, L->w.p_bias, ctx->t, w_up, w_gate,
-                                     L->w.b_up, x_in, D.r, D.d, D.ffn, L->thr_logit,
-                                     ctx->mask_words, ctx->h));
-        }
-    }
-    {
-        ProfScope ps(ctx, K_DOWN_MASK);
-        const int ntiles = cdiv(D.d, pf::kDownCols);
-        const dim3 grid(cdiv(ntiles, 8) * 8);
-        PF_SWITCH_B(B, PF_LAUNCH(ps, pf::k_down_mask<BT>, grid, dim3(pf::kDownThreads),
-                                 pf::down_mask_lds_bytes(D.ffn), st, w_down, L->w.b_down, ctx->h,
-                                 ctx->mask_words, ctx->idx, ctx->count, y, D.d, D.ffn, ntiles));
-    }
-    PF_HIP(ctx, hipGetLastError());
-    return PF_OK;
+    return launch_sparse(ctx, L, x_in, B, nullptr, nullptr, ctx->mask_words, y, ny_out, st);
 }
 
 pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int ny, int d, int B,
@@ -542,7 +492,6 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         if (e != hipSuccess) { st = PF_EHIP; break; }
         if (prop.multiProcessorCount > 0) ctx->num_cu = prop.multiProcessorCount;
         ctx->up_grid_cap = 8 * ctx->num_cu;
-        if (const char *v = getenv("PF_FUSED")) ctx->no_fused = atoi(v) == 0;
         if (const char *v = getenv("PF_DOWN_SPLIT")) {
             int c = atoi(v);
             if (c >= 1 && c <= pf::kDown2MaxSplit) ctx->down_split = c;
