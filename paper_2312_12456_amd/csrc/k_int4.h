@@ -103,7 +103,8 @@ __device__ __forceinline__ void i4_fma_group(const I4Group<U> &g, const float *_
             fma_i4<B>(g.w[u], half_bits_to_float(g.sc[u]), xs + (it0 + u) * kI4Chunk + lane * 4, kpad, acc);
 }
 
-constexpr int kUpI4Threads = 256;
+constexpr int kUpI4Threads = 512;  // rows are long (d up to 12288): fewer, larger workgroups
+                                   // stage x less often (measured best at 512 x 2 per CU)
 constexpr int kUpI4Waves = kUpI4Threads / kWave;
 
 // FC1 (and gate) over listed neurons, int4 weights: the structure of k_up with 2048-element
@@ -207,6 +208,24 @@ __global__ __launch_bounds__(kUpI4Threads) void k_up_i4(
     }
 }
 
+// One exchange of a halving butterfly over lane bit D: of its 2 * NV values a lane keeps the
+// lower NV (bit clear) or the upper NV (bit set), adds the partner's copies of the same
+// columns and gives the rest away.  D and NV are compile-time so the values stay in
+// registers under fixed names.
+template <int D, int NV>
+__device__ __forceinline__ void butterfly_halve(float (&a)[32], int lane)
+{
+    const bool upper = (lane & D) != 0;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const float send = upper ? a[k] : a[k + NV];
+        const float keep = upper ? a[k + NV] : a[k];
+        const float got = (D == 8) ? dpp_f32<0x128>(send)  // row_ror:8 = lane ^ 8 in a row of 16
+                                   : __shfl_xor(send, D, 64);
+        a[k] = keep + got;
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // FC2 over listed neurons, int4 weights, row-split like k_down2: a workgroup owns 256 output
 // columns = one full 128-byte line of nibbles per row (8 lanes x 16 bytes, 32 columns per
@@ -238,6 +257,7 @@ __global__ __launch_bounds__(kDown2I4Threads) void k_down2_i4(
     const rsrc_t wq = make_rsrc(q_down, (uint32_t)ffn * (uint32_t)(d / 2));
     const rsrc_t ws = make_rsrc(s_down, (uint32_t)ffn * (uint32_t)ngroups * 2u);
 
+    PF_TSTAMP(3, 0);
     float acc[B][32], wsum[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) {
@@ -261,6 +281,7 @@ __global__ __launch_bounds__(kDown2I4Threads) void k_down2_i4(
         if (!have_n) {
             n = min(max(*count_p, 0), ffn);
             have_n = true;
+            PF_TSTAMP(3, 1);
         }
         uint4 w[U];
         unsigned short sc[U];
@@ -295,7 +316,9 @@ __global__ __launch_bounds__(kDown2I4Threads) void k_down2_i4(
                     for (int e = 0; e < 8; ++e) acc[b][8 * k + e] = fmaf(hs[b], f[e], acc[b][8 * k + e]);
             }
         }
+        if (r0 == 0) PF_TSTAMP(3, 2);
     }
+    PF_TSTAMP(3, 3);
 
 #pragma unroll
     for (int b = 0; b < B; ++b) {
@@ -303,21 +326,15 @@ __global__ __launch_bounds__(kDown2I4Threads) void k_down2_i4(
         for (int c = 0; c < 32; ++c) acc[b][c] = fmaf(-8.f, wsum[b], acc[b][c]);
         // halving butterfly over the 8 row slots of the wave (lane bits 5, 4, 3): a lane ends
         // with 4 of its 32 columns, summed over the 8 rows
-#pragma unroll
-        for (int D = 32, nv = 16; D >= 8; D >>= 1, nv >>= 1) {
-            const bool upper = (lane & D) != 0;
-#pragma unroll
-            for (int k = 0; k < nv; ++k) {
-                const float send = upper ? acc[b][k] : acc[b][k + nv];
-                const float keep = upper ? acc[b][k + nv] : acc[b][k];
-                acc[b][k] = keep + __shfl_xor(send, D, 64);
-            }
-        }
+        butterfly_halve<32, 16>(acc[b], lane);
+        butterfly_halve<16, 8>(acc[b], lane);
+        butterfly_halve<8, 4>(acc[b], lane);
         const int sub = ((lane >> 5) & 1) * 16 + ((lane >> 4) & 1) * 8 + ((lane >> 3) & 1) * 4;
         *reinterpret_cast<float4 *>(&red[wave][b][cl * 32 + sub]) =
             make_float4(acc[b][0], acc[b][1], acc[b][2], acc[b][3]);
     }
     __syncthreads();
+    PF_TSTAMP(3, 4);
     for (int e = threadIdx.x; e < B * kDown2I4Cols; e += kDown2I4Threads) {
         const int b = e / kDown2I4Cols, c = e % kDown2I4Cols;
         const int oc = tile * kDown2I4Cols + c;
@@ -328,6 +345,7 @@ __global__ __launch_bounds__(kDown2I4Threads) void k_down2_i4(
             part[((size_t)g * B + b) * d + oc] = s;
         }
     }
+    PF_TSTAMP(3, 5);
 }
 
 }  // namespace pf

@@ -39,6 +39,7 @@ struct pf_ctx {
     int max_d = 0, max_ffn = 0, max_r = 0, max_batch = 0;
     int num_cu = 256;
     int up_grid_cap = 2048;
+    int up_grid_cap_i4 = 512;
     int lds_budget = kLdsDefault;  // dynamic LDS a kernel of this context may request
     int down_split = 0;            // PF_DOWN_SPLIT: row groups of FC2 (0 = from the CU count)
     int mfma_min_batch = 4;        // FC1 goes to the matrix cores from this batch size on
@@ -275,7 +276,7 @@ pf_status launch_sparse_i4(pf_ctx *ctx, const pf_layer *L, const float *x, int B
     if (tile < 1) tile = 1;
     if (tile > B) tile = B;
     int up_grid = cdiv(D.ffn, pf::kUpI4Waves);
-    if (up_grid > ctx->up_grid_cap) up_grid = ctx->up_grid_cap;
+    if (up_grid > ctx->up_grid_cap_i4) up_grid = ctx->up_grid_cap_i4;
     const bool gated = D.act == PF_ACT_REGLU;
     for (int b0 = 0; b0 < B; b0 += tile) {
         const int bt = (B - b0) < tile ? (B - b0) : tile;
@@ -492,6 +493,7 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         if (e != hipSuccess) { st = PF_EHIP; break; }
         if (prop.multiProcessorCount > 0) ctx->num_cu = prop.multiProcessorCount;
         ctx->up_grid_cap = 8 * ctx->num_cu;
+        ctx->up_grid_cap_i4 = 2 * ctx->num_cu;
         if (const char *v = getenv("PF_DOWN_SPLIT")) {
             int c = atoi(v);
             if (c >= 1 && c <= pf::kDown2MaxSplit) ctx->down_split = c;
@@ -502,7 +504,7 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         }
         if (const char *v = getenv("PF_UP_GRID")) {
             int c = atoi(v);
-            if (c >= 1 && c <= 65535) ctx->up_grid_cap = c;
+            if (c >= 1 && c <= 65535) ctx->up_grid_cap = ctx->up_grid_cap_i4 = c;
         }
         // larger staged batches need the opt-in LDS size; without it batches are tiled smaller
         if (prop.sharedMemPerBlock >= (size_t)kLdsMax ||
