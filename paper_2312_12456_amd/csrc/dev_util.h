@@ -215,6 +215,33 @@ __device__ __forceinline__ void stage_commit(const Staged<B, S> &st, float *__re
     }
 }
 
+// The same LDS image written by global -> LDS loads that bypass the registers
+// (buffer_load_dwordx4 ... lds): a wave instruction moves 64 x 16 bytes to 1 KB of contiguous
+// LDS, and plane p of a chunk is exactly float4 number p of every lane, so one instruction
+// fills one plane.  Nothing is held in registers, so the whole image of any length and batch
+// is in flight at once (the register form needs one round trip per pass of a long vector).
+// Offsets past the vector read as zeros, which pads the image.  The caller synchronises
+// the block before reading xs.
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+template <int B, int EPL = 8>
+__device__ __forceinline__ void stage_dma(float *__restrict__ xs, const float *__restrict__ v, int K,
+                                          int kpad)
+{
+    constexpr int W = 64 * EPL, PL = EPL / 4;  // chunk width, planes per chunk
+    const rsrc_t r = make_rsrc(v, (uint32_t)B * (uint32_t)K * 4u);
+    const int lane = threadIdx.x & 63;
+    const int wave = wave_uniform(threadIdx.x >> 6), nwaves = blockDim.x >> 6;
+    const int nplanes = (kpad / W) * PL;  // per token; plane q lies at float offset 256 * q
+    for (int q = wave; q < B * nplanes; q += nwaves) {
+        const int b = q / nplanes, pq = q - b * nplanes;
+        const int e = (pq / PL) * W + lane * EPL + 4 * (pq % PL);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            r, (lds_ptr_t)(xs + (size_t)b * kpad + (size_t)pq * 256), 16,
+            e < K ? (int)((uint32_t)(b * K + e) * 4u) : (int)kOobOffset, 0, 0, 0);
+    }
+}
+
 // acc[b] += dot(chunks it0..it0+U-1 of a row (already in g), staged activations of token b)
 template <int B, int U>
 __device__ __forceinline__ void fma_group(const WGroup<U> &g, const float *__restrict__ xs,

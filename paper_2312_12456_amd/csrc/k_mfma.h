@@ -64,6 +64,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     uint64_t *words_lds = dyn_lds64;
     uint32_t *pre_lds = reinterpret_cast<uint32_t *>(words_lds + (FROM_MASK ? nwords : 0));
 
+    PF_TSTAMP(2, 0);
     int n;
     int top_step = 1;
     if (FROM_MASK) {
@@ -81,6 +82,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     const int per_wave = (nsteps + kMfmaWaves - 1) / kMfmaWaves;
     const int s_begin = wave * per_wave, s_end = min(nsteps, s_begin + per_wave);
     const int npass = (n + kMfmaRows - 1) / kMfmaRows;
+    PF_TSTAMP(2, 1);
 
     for (int pass = blockIdx.x; pass < npass; pass += gridDim.x) {
         // the A-operand row of this lane: list slot -> neuron id
@@ -98,6 +100,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
             if (FROM_MASK && ir[0] >= 0) idx_out[jr[0]] = ir[0];
         }
 
+        if (pass == (int)blockIdx.x) PF_TSTAMP(2, 2);
         float4v_t cu = {0.f, 0.f, 0.f, 0.f}, cg = {0.f, 0.f, 0.f, 0.f};
         for (int s0 = s_begin; s0 < s_end; s0 += KU) {
             Half8Bits au[KU], ag[KU];
@@ -129,6 +132,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
                 }
             }
         }
+        if (pass == (int)blockIdx.x) PF_TSTAMP(2, 3);
         // this lane holds C[row 4*kg + e][col row16] of its K slice
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -151,7 +155,9 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
             if (colb < B && j < n) h[(size_t)colb * ffn + j] = i >= 0 ? v : 0.f;
         }
         __syncthreads();
+        if (pass == (int)blockIdx.x) PF_TSTAMP(2, 4);
     }
+    PF_TSTAMP(2, 5);
 }
 
 }  // namespace pf

@@ -42,9 +42,7 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
     const rsrc_t row = row_rsrc(p1, live ? m : 0, d, live);
 
     PF_TSTAMP(0, 0);
-    constexpr int SS = (B >= 4) ? 1 : 4 / B;
-    Staged<B, SS> st;
-    if (!GLUE) stage_issue<B, SS>(st, x, d);
+    if (!GLUE) stage_dma<B>(xs, x, d, kpad);
     WGroup<U> g;
     float scale[B];
     if (GLUE) {
@@ -121,7 +119,6 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
         }
     } else {
         load_group<U>(g, row, 0, lane);
-        stage_commit<B, SS>(st, xs, x, d, kpad);
         __syncthreads();
 #pragma unroll
         for (int b = 0; b < B; ++b) scale[b] = 1.f;
@@ -169,7 +166,6 @@ __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
     __shared__ float logit_s[B][NB];
     // 16 waves per block leave 128 VGPRs per lane: fewer loads in flight at larger batch
     constexpr int U = (B <= 2) ? 4 : 2, R = NB / (kPredOutThreads / kWave);
-    constexpr int SS = (kPredOutThreads >= 1024 || B >= 4) ? 1 : 4 / B;
     const int lane = threadIdx.x & 63, wave = wave_uniform(threadIdx.x >> 6);
     const int nch = (r + kChunk - 1) / kChunk, kpad = nch * kChunk;
     const int n0 = blockIdx.x * NB + wave * R;
@@ -178,15 +174,13 @@ __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
     for (int q = 0; q < R; ++q) rows[q] = row_rsrc(p2, n0 + q, r, true);
 
     PF_TSTAMP(1, 0);
-    Staged<B, SS> st;
-    stage_issue<B, SS>(st, t, r);
+    stage_dma<B>(ts, t, r, kpad);
 #ifndef PF_OUT_PRE
 #define PF_OUT_PRE 2  // rows whose loads are issued before the block barrier
 #endif
     WGroup<U> g[R];
 #pragma unroll
     for (int q = 0; q < PF_OUT_PRE; ++q) load_group<U>(g[q], rows[q], 0, lane);
-    stage_commit<B, SS>(st, ts, t, r, kpad);
     __syncthreads();
 #pragma unroll
     for (int q = PF_OUT_PRE; q < R; ++q) load_group<U>(g[q], rows[q], 0, lane);
