@@ -130,13 +130,9 @@ __global__ __launch_bounds__(kUpI4Threads) void k_up_i4(
     uint64_t *words_lds = reinterpret_cast<uint64_t *>(xs + (size_t)B * kpad + kStageScrap);
     uint32_t *pre_lds = reinterpret_cast<uint32_t *>(words_lds + nwords);
 
-    constexpr bool DMA = (B >= 2);  // as in k_up
-    constexpr int SS = 4;
-    Staged<DMA ? 1 : B, DMA ? 1 : SS> st;
-    if constexpr (DMA)
-        stage_dma<B, kI4Epl>(xs, x, d, kpad);
-    else
-        stage_issue<B, SS>(st, x, d);
+    constexpr int SS = (B >= 4) ? 1 : 4 / B;
+    Staged<B, SS> st;
+    stage_issue<B, SS>(st, x, d);
     int n;
     if (FROM_MASK) {
         n = (int)mask_prefix<kUpI4Threads>(mask_words, nwords, words_lds, pre_lds, wave_tot);
@@ -169,7 +165,7 @@ __global__ __launch_bounds__(kUpI4Threads) void k_up_i4(
     i4_load_group<U>(gu, ru, 0, lane);
     if (GATED) i4_load_group<U>(gg, rg, 0, lane);
 
-    if constexpr (!DMA) stage_commit<B, SS, kI4Epl>(st, xs, x, d, kpad);
+    stage_commit<B, SS, kI4Epl>(st, xs, x, d, kpad);
     __syncthreads();
 
     while (j < n) {  // wave-uniform; no block-level synchronisation inside

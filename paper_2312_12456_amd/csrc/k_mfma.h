@@ -1,14 +1,19 @@
 // FC1 over the listed neurons for a batch of tokens as a matrix-core contraction
 // (PowerInfer Sec. 8.2, batching: the active set is the union over the batch, so the gathered
 // rows form a dense [k x d] block that multiplies [d x B]).  At batch 1 the row-sparse GEMV is
-// pure HBM streaming; from a few tokens on, B FMAs per weight make the vector ALUs the
-// limiter before HBM saturates, and v_mfma_f32_16x16x32_f16 does the same work in 1/8 of
-// the issue slots.  M = 16 gathered rows, N = 16 batch columns (tokens >= B read as zero),
-// K = 32 elements of d per instruction.
+// pure HBM streaming; from a few tokens on, B FMAs and B LDS reads per weight make the vector
+// path the limiter before HBM saturates, and v_mfma_f32_16x16x32_f16 does the same work in a
+// fraction of the issue slots.  M = 16 gathered rows, N = 16 batch columns (tokens >= B read
+// as zero), K = 32 elements of d per instruction.
 // Operand layout (verified on the device): lane l supplies A[row l%16][8 halfs from k = 8*(l/16)]
 // and B[same 8 k][col l%16]; it receives C[rows 4*(l/16) .. +3][col l%16].
 // Activations stay fp32-exact: x is split into fp16 hi + fp16 lo (x = hi + lo to 2^-21) and
 // each step issues two MFMAs.
+//
+// Weights do not go to the registers in operand order: a load in which each quarter-wave
+// touches 16 different rows costs the memory pipeline 16 line look-ups for 256 bytes.
+// Instead they go global -> LDS (buffer_load ... lds) in instructions that read 512
+// contiguous bytes of each of two rows, and the A operands are read back from LDS.
 #pragma once
 #include "dev_util.h"
 #include "k_predict.h"
@@ -20,8 +25,25 @@ typedef float float4v_t __attribute__((ext_vector_type(4)));
 
 constexpr int kMfmaThreads = 512;
 constexpr int kMfmaWaves = kMfmaThreads / kWave;  // the waves of a block split K between them
-constexpr int kMfmaRows = 16;                     // list slots per block pass: one MFMA tile
-constexpr int kMfmaKU = 8;                        // K steps (of 32) whose loads are in flight together
+constexpr int kMfmaRows = 32;                     // list slots per block pass: two MFMA tiles
+constexpr int kMfmaKC = 128;                      // elements of d per chunk (4 MFMA K steps)
+constexpr int kMfmaSteps = kMfmaKC / 32;
+// LDS image of one chunk of one matrix: 32 rows x 256 bytes, written by 8 instructions of
+// 4 rows each (a quarter-wave per row, 16 pieces of 16 bytes)
+constexpr int kMfmaSlotBytes = kMfmaRows * kMfmaKC * 2;
+
+// dynamic LDS of k_up_mfma: [mask words | prefix] when compacting itself, then one slot per
+// wave and matrix
+inline size_t up_mfma_mask_bytes(int ffn, bool from_mask)
+{
+    if (!from_mask) return 0;
+    const size_t nwords = (size_t)ffn / 64;
+    return ((nwords * 8 + (nwords + 1) * 4 + 63) / 64) * 64;
+}
+inline size_t up_mfma_lds_bytes(int ffn, bool from_mask, bool gated)
+{
+    return up_mfma_mask_bytes(ffn, from_mask) + (size_t)kMfmaWaves * (gated ? 2 : 1) * kMfmaSlotBytes;
+}
 
 union Half8Bits {
     uint4 u;
@@ -40,10 +62,32 @@ __device__ __forceinline__ void split_hi_lo(const float4 &a, const float4 &b, ha
     }
 }
 
-// grid = any; blocks stride over passes of 16 list slots; the 8 waves of a block each take
-// an eighth of the K steps of the same 16 rows (so that a pass has 8 x 16 rows x 512 bytes
-// in flight instead of one wave walking d alone) and their C tiles are added in LDS in
-// wave order.  d % 32 == 0, B <= 16.
+// Put chunk `c` of the 32 rows of a pass in flight towards `slot`.  Instruction i moves rows
+// 4i .. 4i+3, one per quarter-wave, 16 pieces of 16 bytes each: a row's 256 bytes are two
+// whole lines.  Row R stores piece p at position p ^ swz(R), swz(R) = 2 * (R & 3) + ((R >> 2) & 1),
+// so that the 8 rows a group of 8 lanes reads together (same piece) fall into 8 different
+// 16-byte bank groups.  rowoff[i] = byte offset of this lane's row of instruction i in the
+// matrix (kOobOffset: no row).
+__device__ __forceinline__ int mfma_swz(int row) { return 2 * (row & 3) + ((row >> 2) & 1); }
+
+__device__ __forceinline__ void mfma_issue_chunk(rsrc_t w, char *slot, const uint32_t (&rowoff)[8],
+                                                 int c, int d, int lane)
+{
+    const int q = lane >> 4, p = lane & 15;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int piece = p ^ (2 * q + (i & 1));  // = p ^ swz(4i + q)
+        const int k = c * kMfmaKC + piece * 8;
+        const uint32_t off = (k < d && rowoff[i] != kOobOffset) ? rowoff[i] + (uint32_t)k * 2u : kOobOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(w, (lds_ptr_t)(slot + i * 1024), 16, (int)off, 0, 0, 0);
+    }
+}
+
+// grid = G blocks; block b owns the list slots [b * rpb, (b + 1) * rpb), rpb = ceil(n / G),
+// in passes of 32 (an even share of the rows for every CU: with whole tiles dealt round-robin
+// the CUs that get one tile more than the others set the kernel's time).  The 8 waves of a
+// block take the chunks of d round-robin (wave w: chunks w, w + 8, ...) for the same rows and
+// their C tiles are added in LDS in wave order.  d % 32 == 0, B <= 16.
 template <int ACT, bool FROM_MASK>
 __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
@@ -54,15 +98,18 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
 {
     extern __shared__ uint64_t dyn_lds64[];
     __shared__ uint32_t wave_tot[kMfmaWaves];
-    __shared__ float ctile[kMfmaWaves][2][256];  // per wave: C of up, C of gate (16 x 16 each)
-    __shared__ int irow[16];
+    __shared__ int irow[kMfmaRows];
     constexpr bool GATED = (ACT == 1);
-    constexpr int KU = kMfmaKU;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int NM = GATED ? 2 : 1;
+    const int lane = threadIdx.x & 63, wave = wave_uniform(threadIdx.x >> 6);
     const int row16 = lane & 15, kg = lane >> 4;
     const int nwords = ffn / 64;
     uint64_t *words_lds = dyn_lds64;
     uint32_t *pre_lds = reinterpret_cast<uint32_t *>(words_lds + (FROM_MASK ? nwords : 0));
+    const size_t mask_bytes =
+        FROM_MASK ? (((size_t)nwords * 8 + ((size_t)nwords + 1) * 4 + 63) / 64) * 64 : 0;
+    char *slots = reinterpret_cast<char *>(dyn_lds64) + mask_bytes;
+    char *slot = slots + (size_t)wave * NM * kMfmaSlotBytes;  // this wave's: up, then gate
 
     PF_TSTAMP(2, 0);
     int n;
@@ -78,84 +125,127 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     const rsrc_t wg = make_rsrc(GATED ? w_gate : w_up, (uint32_t)ffn * (uint32_t)d * 2u);
     const rsrc_t xr = make_rsrc(x, (uint32_t)B * (uint32_t)d * 4u);
     const uint32_t xoff = row16 < B ? ((uint32_t)row16 * (uint32_t)d + (uint32_t)kg * 8u) * 4u : kOobOffset;
-    const int nsteps = d / 32;
-    const int per_wave = (nsteps + kMfmaWaves - 1) / kMfmaWaves;
-    const int s_begin = wave * per_wave, s_end = min(nsteps, s_begin + per_wave);
-    const int npass = (n + kMfmaRows - 1) / kMfmaRows;
+    const int nchunks = (d + kMfmaKC - 1) / kMfmaKC;
+    const int rpb = (n + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int j_begin = min(n, (int)blockIdx.x * rpb), j_end = min(n, j_begin + rpb);
+    // this lane's A operands of tile t, K step s: row 16t + row16, piece 4s + kg
+    const int arow0 = row16 * (kMfmaKC * 2), aswz = mfma_swz(row16);  // swz(16 + r) == swz(r)
     PF_TSTAMP(2, 1);
 
-    for (int pass = blockIdx.x; pass < npass; pass += gridDim.x) {
-        // the A-operand row of this lane: list slot -> neuron id
-        const int jr[1] = {pass * kMfmaRows + row16};
-        int ir[1];
+    for (int j0 = j_begin; j0 < j_end; j0 += kMfmaRows) {
+        const bool two = j_end - j0 > 16;  // block-uniform: the second tile has rows
+        // list slot -> neuron id for the two rows whose A operands this lane supplies
+        const int jr[2] = {j0 + row16 < j_end ? j0 + row16 : n, j0 + 16 + row16 < j_end ? j0 + 16 + row16 : n};
+        int ir[2];
         if (FROM_MASK) {
-            select_set_bits_lane<1>(words_lds, pre_lds, nwords, top_step, n, jr, ir);
+            select_set_bits_lane<2>(words_lds, pre_lds, nwords, top_step, n, jr, ir);
         } else {
-            ir[0] = jr[0] < n ? idx_in[jr[0]] : -1;
-            if ((unsigned)ir[0] >= (unsigned)ffn) ir[0] = -1;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                ir[t] = jr[t] < n ? idx_in[jr[t]] : -1;
+                if ((unsigned)ir[t] >= (unsigned)ffn) ir[t] = -1;
+            }
         }
-        const uint32_t aoff = ir[0] >= 0 ? ((uint32_t)ir[0] * (uint32_t)d + (uint32_t)kg * 8u) * 2u : kOobOffset;
         if (wave == 0 && kg == 0) {
-            irow[row16] = ir[0];
-            if (FROM_MASK && ir[0] >= 0) idx_out[jr[0]] = ir[0];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                irow[16 * t + row16] = ir[t];
+                if (FROM_MASK && ir[t] >= 0) idx_out[jr[t]] = ir[t];
+            }
         }
+        // byte offsets of the rows this lane fetches: instruction i -> row 4i + lane / 16
+        uint32_t rowoff[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int id = __shfl(ir[i >> 2], (4 * i + kg) & 15, 64);
+            rowoff[i] = id >= 0 ? (uint32_t)id * (uint32_t)d * 2u : kOobOffset;
+        }
+        if (j0 == j_begin) PF_TSTAMP(2, 2);
 
-        if (pass == (int)blockIdx.x) PF_TSTAMP(2, 2);
-        float4v_t cu = {0.f, 0.f, 0.f, 0.f}, cg = {0.f, 0.f, 0.f, 0.f};
-        for (int s0 = s_begin; s0 < s_end; s0 += KU) {
-            Half8Bits au[KU], ag[KU];
-            float4 xa[KU], xb[KU];
+        float4v_t cu[2], cg[2];
 #pragma unroll
-            for (int u = 0; u < KU; ++u) {
-                const bool live = s0 + u < s_end;
-                const uint32_t kb = (uint32_t)(s0 + u) * 32u;  // element offset of this K step
-                const uint32_t o = live && aoff != kOobOffset ? aoff + kb * 2u : kOobOffset;
-                au[u].u = ld16_stream(wu, o);
-                if (GATED) ag[u].u = ld16_stream(wg, o);
+        for (int t = 0; t < 2; ++t) {
+            cu[t] = (float4v_t){0.f, 0.f, 0.f, 0.f};
+            cg[t] = (float4v_t){0.f, 0.f, 0.f, 0.f};
+        }
+        int c = wave;
+        if (c < nchunks) {
+            mfma_issue_chunk(wu, slot, rowoff, c, d, lane);
+            if (GATED) mfma_issue_chunk(wg, slot + kMfmaSlotBytes, rowoff, c, d, lane);
+        }
+        while (c < nchunks) {  // wave-uniform
+            float4 xa[kMfmaSteps], xb[kMfmaSteps];
+#pragma unroll
+            for (int s = 0; s < kMfmaSteps; ++s) {
+                const int k = c * kMfmaKC + s * 32;
+                const uint32_t o = (k < d && xoff != kOobOffset) ? xoff + (uint32_t)k * 4u : kOobOffset;
+                xa[s] = ld16_f32(xr, o);
+                xb[s] = ld16_f32(xr, o != kOobOffset ? o + 16u : kOobOffset);
             }
+            Half8Bits au[2][kMfmaSteps], ag[2][kMfmaSteps];
 #pragma unroll
-            for (int u = 0; u < KU; ++u) {
-                const bool live = s0 + u < s_end;
-                const uint32_t kb = (uint32_t)(s0 + u) * 32u;
-                xa[u] = ld16_f32(xr, live && xoff != kOobOffset ? xoff + kb * 4u : kOobOffset);
-                xb[u] = ld16_f32(xr, live && xoff != kOobOffset ? xoff + kb * 4u + 16u : kOobOffset);
-            }
+            for (int t = 0; t < 2; ++t) {
+                if (t == 1 && !two) break;
 #pragma unroll
-            for (int u = 0; u < KU; ++u) {
-                half8_t hi, lo;
-                split_hi_lo(xa[u], xb[u], hi, lo);
-                cu = __builtin_amdgcn_mfma_f32_16x16x32_f16(au[u].h, hi, cu, 0, 0, 0);
-                cu = __builtin_amdgcn_mfma_f32_16x16x32_f16(au[u].h, lo, cu, 0, 0, 0);
-                if (GATED) {
-                    cg = __builtin_amdgcn_mfma_f32_16x16x32_f16(ag[u].h, hi, cg, 0, 0, 0);
-                    cg = __builtin_amdgcn_mfma_f32_16x16x32_f16(ag[u].h, lo, cg, 0, 0, 0);
+                for (int s = 0; s < kMfmaSteps; ++s) {
+                    const int at = t * 16 * (kMfmaKC * 2) + arow0 + ((4 * s + kg) ^ aswz) * 16;
+                    au[t][s].u = *reinterpret_cast<const uint4 *>(slot + at);
+                    if (GATED) ag[t][s].u = *reinterpret_cast<const uint4 *>(slot + kMfmaSlotBytes + at);
                 }
             }
-        }
-        if (pass == (int)blockIdx.x) PF_TSTAMP(2, 3);
-        // this lane holds C[row 4*kg + e][col row16] of its K slice
+            const int cn = c + kMfmaWaves;
+            if (cn < nchunks) {  // refill the slot once its contents are in the registers
+                __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+                mfma_issue_chunk(wu, slot, rowoff, cn, d, lane);
+                if (GATED) mfma_issue_chunk(wg, slot + kMfmaSlotBytes, rowoff, cn, d, lane);
+            }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            ctile[wave][0][(kg * 4 + e) * 16 + row16] = cu[e];
-            if (GATED) ctile[wave][1][(kg * 4 + e) * 16 + row16] = cg[e];
+            for (int s = 0; s < kMfmaSteps; ++s) {
+                half8_t hi, lo;
+                split_hi_lo(xa[s], xb[s], hi, lo);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    if (t == 1 && !two) break;
+                    cu[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(au[t][s].h, hi, cu[t], 0, 0, 0);
+                    cu[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(au[t][s].h, lo, cu[t], 0, 0, 0);
+                    if (GATED) {
+                        cg[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ag[t][s].h, hi, cg[t], 0, 0, 0);
+                        cg[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ag[t][s].h, lo, cg[t], 0, 0, 0);
+                    }
+                }
+            }
+            c = cn;
         }
+        if (j0 == j_begin) PF_TSTAMP(2, 3);
+        // this lane holds C[row 4*kg + e][col row16] of its chunks, per tile; the wave's slot
+        // is free now: [tile][up | gate][256]
+        float *ctile = reinterpret_cast<float *>(slot);
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                ctile[(t * 2) * 256 + (kg * 4 + e) * 16 + row16] = cu[t][e];
+                if (GATED) ctile[(t * 2 + 1) * 256 + (kg * 4 + e) * 16 + row16] = cg[t][e];
+            }
         __syncthreads();
-        if (threadIdx.x < 256) {
-            const int row = threadIdx.x >> 4, colb = threadIdx.x & 15;
+        {
+            const int t = threadIdx.x >> 8, e = threadIdx.x & 255;
+            const int row = 16 * t + (e >> 4), colb = e & 15;
             float su = 0.f, sg = 0.f;
 #pragma unroll
             for (int wv = 0; wv < kMfmaWaves; ++wv) {
-                su += ctile[wv][0][threadIdx.x];
-                if (GATED) sg += ctile[wv][1][threadIdx.x];
+                const float *ct = reinterpret_cast<const float *>(slots + (size_t)wv * NM * kMfmaSlotBytes);
+                su += ct[(t * 2) * 256 + e];
+                if (GATED) sg += ct[(t * 2 + 1) * 256 + e];
             }
             const int i = irow[row];
-            const int j = pass * kMfmaRows + row;
+            const int j = j0 + row;
             const float bias = (b_up != nullptr && i >= 0) ? b_up[i] : 0.f;
             const float v = GATED ? fmaxf(sg + bias, 0.f) * su : fmaxf(su + bias, 0.f);
-            if (colb < B && j < n) h[(size_t)colb * ffn + j] = i >= 0 ? v : 0.f;
+            if (colb < B && j < j_end) h[(size_t)colb * ffn + j] = i >= 0 ? v : 0.f;
         }
         __syncthreads();
-        if (pass == (int)blockIdx.x) PF_TSTAMP(2, 4);
+        if (j0 == j_begin) PF_TSTAMP(2, 4);
     }
     PF_TSTAMP(2, 5);
 }

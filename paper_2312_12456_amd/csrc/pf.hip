@@ -40,6 +40,7 @@ struct pf_ctx {
     int num_cu = 256;
     int up_grid_cap = 2048;
     int up_grid_cap_i4 = 512;
+    int mfma_grid = 256;
     int lds_budget = kLdsDefault;  // dynamic LDS a kernel of this context may request
     int down_split = 0;            // PF_DOWN_SPLIT: row groups of FC2 (0 = from the CU count)
     int mfma_min_batch = 4;        // FC1 goes to the matrix cores from this batch size on
@@ -147,6 +148,15 @@ hipError_t allow_lds_for_batch()
     return e;
 }
 
+hipError_t allow_lds_mfma()
+{
+    hipError_t e = allow_lds(pf::k_up_mfma<0, false>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<0, true>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, false>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, true>);
+    return e;
+}
+
 hipError_t allow_lds_all()
 {
     hipError_t e = allow_lds_for_batch<1>();
@@ -157,6 +167,7 @@ hipError_t allow_lds_all()
     if (e == hipSuccess) e = allow_lds_for_batch<6>();
     if (e == hipSuccess) e = allow_lds_for_batch<7>();
     if (e == hipSuccess) e = allow_lds_for_batch<8>();
+    if (e == hipSuccess) e = allow_lds_mfma();
     return e;
 }
 
@@ -337,16 +348,16 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     const bool from_mask = mask_words != nullptr;
     const size_t extra = from_mask ? pf::up_mask_lds_bytes(D.ffn) : 0;
     const int tile = batch_tile(ctx, D.d, B, extra + 1024);
+    const bool gated = D.act == PF_ACT_REGLU;
     int up_grid = cdiv(D.ffn, pf::kUpWaves);
     if (up_grid > ctx->up_grid_cap) up_grid = ctx->up_grid_cap;
-    const bool gated = D.act == PF_ACT_REGLU;
-    const bool mfma = B >= ctx->mfma_min_batch && D.d % 32 == 0;
+    const size_t mfma_lds = pf::up_mfma_lds_bytes(D.ffn, from_mask, gated);
+    const bool mfma = B >= ctx->mfma_min_batch && D.d % 32 == 0 && mfma_lds <= (size_t)ctx->lds_budget;
     if (mfma) {  // the whole batch in one launch: tokens are the N columns of the tile
-        int grid = cdiv(D.ffn, pf::kMfmaRows);
-        if (grid > ctx->up_grid_cap) grid = ctx->up_grid_cap;
+        const int grid = ctx->mfma_grid;  // one block per CU (its LDS image fills the CU)
         ProfScope ps(ctx, K_UP_MFMA);
 #define PF_UPM(ACT, FM)                                                                           \
-    PF_LAUNCH(ps, (pf::k_up_mfma<ACT, FM>), dim3(grid), dim3(pf::kMfmaThreads), extra, st, w_up,  \
+    PF_LAUNCH(ps, (pf::k_up_mfma<ACT, FM>), dim3(grid), dim3(pf::kMfmaThreads), mfma_lds, st, w_up, \
               w_gate, L->w.b_up, x, B, idx_in, count_in, mask_words, ctx->idx, ctx->count, ctx->h, \
               D.d, D.ffn)
         if (gated && from_mask) { PF_UPM(1, true); }
@@ -494,6 +505,11 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         if (prop.multiProcessorCount > 0) ctx->num_cu = prop.multiProcessorCount;
         ctx->up_grid_cap = 8 * ctx->num_cu;
         ctx->up_grid_cap_i4 = 2 * ctx->num_cu;
+        ctx->mfma_grid = ctx->num_cu;
+        if (const char *v = getenv("PF_MFMA_GRID")) {
+            int c = atoi(v);
+            if (c >= 1 && c <= 65535) ctx->mfma_grid = c;
+        }
         if (const char *v = getenv("PF_DOWN_SPLIT")) {
             int c = atoi(v);
             if (c >= 1 && c <= pf::kDown2MaxSplit) ctx->down_split = c;
