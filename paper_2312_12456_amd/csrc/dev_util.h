@@ -47,6 +47,25 @@ __device__ __forceinline__ float wave_sum(float v)
     return (a + b) + (c + d);
 }
 
+// One exchange of a halving butterfly over lane bit D (8, 16 or 32): of its 2 * NV values a
+// lane keeps the
+// lower NV (bit clear) or the upper NV (bit set), adds the partner's copies of the same
+// columns and gives the rest away.  D and NV are compile-time so the values stay in
+// registers under fixed names.
+template <int D, int NV, int N>
+__device__ __forceinline__ void butterfly_halve(float (&a)[N], int lane)
+{
+    const bool upper = (lane & D) != 0;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const float send = upper ? a[k] : a[k + NV];
+        const float keep = upper ? a[k + NV] : a[k];
+        const float got = (D == 8) ? dpp_f32<0x128>(send)  // row_ror:8 = lane ^ 8 in a row of 16
+                                   : __shfl_xor(send, D, 64);
+        a[k] = keep + got;
+    }
+}
+
 // Buffer resources: every weight and activation load goes through a raw buffer descriptor
 // (base, byte size) held in scalar registers.  Lanes whose offset lies past the end get
 // zeros from the hardware, so loads need no branches -- which also lets the compiler count

@@ -208,24 +208,6 @@ __global__ __launch_bounds__(kUpI4Threads) void k_up_i4(
     }
 }
 
-// One exchange of a halving butterfly over lane bit D: of its 2 * NV values a lane keeps the
-// lower NV (bit clear) or the upper NV (bit set), adds the partner's copies of the same
-// columns and gives the rest away.  D and NV are compile-time so the values stay in
-// registers under fixed names.
-template <int D, int NV>
-__device__ __forceinline__ void butterfly_halve(float (&a)[32], int lane)
-{
-    const bool upper = (lane & D) != 0;
-#pragma unroll
-    for (int k = 0; k < NV; ++k) {
-        const float send = upper ? a[k] : a[k + NV];
-        const float keep = upper ? a[k + NV] : a[k];
-        const float got = (D == 8) ? dpp_f32<0x128>(send)  // row_ror:8 = lane ^ 8 in a row of 16
-                                   : __shfl_xor(send, D, 64);
-        a[k] = keep + got;
-    }
-}
-
 // ---------------------------------------------------------------------------------------
 // FC2 over listed neurons, int4 weights, row-split like k_down2: a workgroup owns 256 output
 // columns = one full 128-byte line of nibbles per row (8 lanes x 16 bytes, 32 columns per

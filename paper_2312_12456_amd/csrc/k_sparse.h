@@ -170,11 +170,13 @@ __global__ __launch_bounds__(kDown2Threads) void k_down2(
     const bool colok = col < d;
     const rsrc_t wd = make_rsrc(w_down, (uint32_t)ffn * (uint32_t)d * 2u);
 
-    float acc[B][8];
+    PF_TSTAMP(3, 0);
+    // token b, column e of this lane -> acc[8 b + e]; padded to a power of two tokens for the
+    // halving butterfly of the epilogue
+    constexpr int BP = B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : 8;
+    float acc[BP * 8];
 #pragma unroll
-    for (int b = 0; b < B; ++b)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
+    for (int f = 0; f < BP * 8; ++f) acc[f] = 0.f;
 
     int n = 0;
     bool have_n = false;
@@ -192,6 +194,7 @@ __global__ __launch_bounds__(kDown2Threads) void k_down2(
         if (!have_n) {
             n = min(max(*count_p, 0), ffn);
             have_n = true;
+            PF_TSTAMP(3, 1);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -209,31 +212,36 @@ __global__ __launch_bounds__(kDown2Threads) void k_down2(
 #pragma unroll
             for (int b = 0; b < B; ++b) {
                 const float s = hv[u][b];
-                acc[b][0] = fmaf(s, f0, acc[b][0]);
-                acc[b][1] = fmaf(s, f1, acc[b][1]);
-                acc[b][2] = fmaf(s, f2, acc[b][2]);
-                acc[b][3] = fmaf(s, f3, acc[b][3]);
-                acc[b][4] = fmaf(s, f4, acc[b][4]);
-                acc[b][5] = fmaf(s, f5, acc[b][5]);
-                acc[b][6] = fmaf(s, f6, acc[b][6]);
-                acc[b][7] = fmaf(s, f7, acc[b][7]);
+                acc[8 * b + 0] = fmaf(s, f0, acc[8 * b + 0]);
+                acc[8 * b + 1] = fmaf(s, f1, acc[8 * b + 1]);
+                acc[8 * b + 2] = fmaf(s, f2, acc[8 * b + 2]);
+                acc[8 * b + 3] = fmaf(s, f3, acc[8 * b + 3]);
+                acc[8 * b + 4] = fmaf(s, f4, acc[8 * b + 4]);
+                acc[8 * b + 5] = fmaf(s, f5, acc[8 * b + 5]);
+                acc[8 * b + 6] = fmaf(s, f6, acc[8 * b + 6]);
+                acc[8 * b + 7] = fmaf(s, f7, acc[8 * b + 7]);
             }
         }
+        if (r0 == 0) PF_TSTAMP(3, 2);
     }
+    PF_TSTAMP(3, 3);
 
-    // sum the 8 row slots of the wave (lane bits 3..5), then the 8 waves through LDS
+    // sum the 8 row slots of the wave (lane bits 5, 4, 3) with a halving butterfly: a lane ends
+    // with BP of its 8 BP values, flat indices [BP * slot, BP * (slot + 1)); then the 8 waves
+    // through LDS
+    butterfly_halve<32, BP * 4>(acc, lane);
+    butterfly_halve<16, BP * 2>(acc, lane);
+    butterfly_halve<8, BP>(acc, lane);
+    {
+        const int slot = ((lane >> 5) & 1) * 4 + ((lane >> 4) & 1) * 2 + ((lane >> 3) & 1);
 #pragma unroll
-    for (int b = 0; b < B; ++b) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float v = acc[b][e];
-            v += dpp_f32<0x128>(v);  // row_ror:8 -> lane ^ 8 within a row of 16
-            v += __shfl_xor(v, 16, 64);
-            v += __shfl_xor(v, 32, 64);
-            if (lane < 8) red[wave][b][cl * 8 + e] = v;
+        for (int k = 0; k < BP; ++k) {
+            const int f = BP * slot + k, b = f >> 3, e = f & 7;
+            if (b < B) red[wave][b][cl * 8 + e] = acc[k];
         }
     }
     __syncthreads();
+    PF_TSTAMP(3, 4);
     if (threadIdx.x < B * kDown2Cols) {
         const int b = threadIdx.x / kDown2Cols, c = threadIdx.x % kDown2Cols;
         const int oc = tile * kDown2Cols + c;
@@ -244,6 +252,7 @@ __global__ __launch_bounds__(kDown2Threads) void k_down2(
             part[((size_t)g * B + b) * d + oc] = s;
         }
     }
+    PF_TSTAMP(3, 5);
 }
 
 // y[b][c] = sum of the P partials in order (for callers that need FC2's output itself).

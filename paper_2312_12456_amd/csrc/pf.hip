@@ -154,6 +154,8 @@ hipError_t allow_lds_mfma()
     if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<0, true>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, false>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, true>);
+    if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<1, 256, 0>);
+    if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<4, 64, 1>);
     return e;
 }
 
@@ -211,6 +213,16 @@ struct ProfScope {
     } while (0)
 
 // ---- launches ------------------------------------------------------------------------
+pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int ny, int d, int B,
+                      float *x_next, hipStream_t st);
+
+// The predictor runs on the matrix cores from the same batch size on as FC1 (row length a
+// multiple of 32, and the opt-in LDS size for its 64 KB of slots + static LDS).
+inline bool pred_mfma(const pf_ctx *ctx, int K, int B)
+{
+    return B >= ctx->mfma_min_batch && K % 32 == 0 && ctx->lds_budget > kLdsDefault;
+}
+
 // Predictor hidden layer.  With glue_y the layer input is formed inside the kernel as
 // norm(x + glue_y) and also written to x_new.
 pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
@@ -219,6 +231,20 @@ pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const fl
     const pf_layer_desc &D = L->desc;
     if (!L->w.p1 || !L->w.p2) return fail(ctx, PF_EINVAL, "layer has no predictor weights");
     const __half *p1 = static_cast<const __half *>(L->w.p1);
+    if (pred_mfma(ctx, D.d, B)) {
+        // a batch on the matrix cores; the glue, if any, as a kernel of its own in front
+        if (glue_y) {
+            pf_status s = launch_glue(ctx, x, glue_y, glue_ny, D.d, B, x_new, st);
+            if (s != PF_OK) return s;
+            x = x_new;
+        }
+        ProfScope ps(ctx, K_PRED_HIDDEN);
+        PF_LAUNCH(ps, (pf::k_rows_mfma<1, 256, 0>), dim3(cdiv(D.r, 16)), dim3(pf::kMfmaThreads),
+                  (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p1, x, B, D.d, D.r,
+                  (const float *)nullptr, 0.f, ctx->t, (uint64_t *)nullptr);
+        PF_HIP(ctx, hipGetLastError());
+        return PF_OK;
+    }
     // hidden layer, in batch tiles that fit LDS
     const int tile = batch_tile(ctx, D.d, B, 1024);
     for (int b0 = 0; b0 < B; b0 += tile) {
@@ -252,6 +278,14 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
     if (s != PF_OK) return s;
     const pf_layer_desc &D = L->desc;
     const __half *p2 = static_cast<const __half *>(L->w.p2);
+    if (pred_mfma(ctx, D.r, B)) {
+        ProfScope ps(ctx, K_PRED_OUT);
+        PF_LAUNCH(ps, (pf::k_rows_mfma<4, 64, 1>), dim3(D.ffn / 64), dim3(pf::kMfmaThreads),
+                  (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p2, (const float *)ctx->t, B, D.r,
+                  D.ffn, L->w.p_bias, L->thr_logit, scores, mask_words);
+        PF_HIP(ctx, hipGetLastError());
+        return PF_OK;
+    }
     // output layer over the whole batch (its staged vector is only B * r floats)
     const size_t lds = ((size_t)B * kpad_of(D.r) + pf::kStageScrap) * sizeof(float);
     const dim3 grid(D.ffn / pf::kPredOutNeurons);
