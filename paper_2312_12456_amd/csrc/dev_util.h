@@ -10,6 +10,37 @@ namespace pf {
 constexpr int kWave = 64;      // CDNA wavefront width
 constexpr int kChunk = 512;    // elements of a row one wave covers per 16-byte load (64 lanes x 8 fp16)
 
+// FC1 outputs are kept slot-major, h[list slot][token] with this many floats per slot, so that
+// FC2 fetches all tokens of a slot with one or two vector loads.
+constexpr __host__ __device__ int h_stride(int B) { return B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : 8; }
+
+// The hs floats of slot j (hs = 1, 2, 4 or 8) into hv[0 .. B).
+template <int B>
+__device__ __forceinline__ void load_h_slot(const float *__restrict__ h, int j, float (&hv)[B])
+{
+    constexpr int HS = h_stride(B);
+    const float *p = h + (size_t)j * HS;
+    float t[HS];
+    if (HS == 1) {
+        t[0] = p[0];
+    } else if (HS == 2) {
+        const float2 a = *reinterpret_cast<const float2 *>(p);
+        t[0] = a.x;
+        t[HS > 1 ? 1 : 0] = a.y;
+    } else {
+#pragma unroll
+        for (int q = 0; q < HS / 4; ++q) {
+            const float4 a = *reinterpret_cast<const float4 *>(p + 4 * q);
+            t[(4 * q + 0) % HS] = a.x;
+            t[(4 * q + 1) % HS] = a.y;
+            t[(4 * q + 2) % HS] = a.z;
+            t[(4 * q + 3) % HS] = a.w;
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < B; ++b) hv[b] = t[b];
+}
+
 // Phase timestamps for kernel tuning, compiled in only with -DPF_TRACE: thread 0 of a block
 // stores the 100 MHz wall clock at a few program points into a host-provided buffer.
 #ifdef PF_TRACE

@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     const float *__restrict__ b_up, const float *__restrict__ x, int B,
     const int32_t *__restrict__ idx_in, const int32_t *__restrict__ count_in,
     const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
-    int32_t *__restrict__ count_out, float *__restrict__ h, int d, int ffn)
+    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn)
 {
     extern __shared__ uint64_t dyn_lds64[];
     __shared__ uint32_t wave_tot[kMfmaWaves];
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
             const int j = j0 + row;
             const float bias = (b_up != nullptr && i >= 0) ? b_up[i] : 0.f;
             const float v = GATED ? fmaxf(sg + bias, 0.f) * su : fmaxf(su + bias, 0.f);
-            if (colb < B && j < j_end) h[(size_t)colb * ffn + j] = i >= 0 ? v : 0.f;
+            if (colb < B && j < j_end) h[(size_t)j * hs + colb] = i >= 0 ? v : 0.f;
         }
         __syncthreads();
         if (j0 == j_begin) PF_TSTAMP(2, 4);

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
     const float *__restrict__ b_up, const float *__restrict__ x,
     const int32_t *__restrict__ idx_in, const int32_t *__restrict__ count_in,
     const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
-    int32_t *__restrict__ count_out, float *__restrict__ h, int d, int ffn)
+    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn)
 {
     extern __shared__ float xs[];
     __shared__ uint32_t wave_tot[kUpWaves];
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
             } else {
                 v = fmaxf(wave_sum(au[b]) + bias, 0.f);
             }
-            if (lane == 0) h[(size_t)b * ffn + jcur] = vcur ? v : 0.f;
+            if (lane == 0) h[(size_t)jcur * hs + b] = vcur ? v : 0.f;
         }
     }
     PF_TSTAMP(2, 4);
@@ -188,8 +188,7 @@ __global__ __launch_bounds__(kDown2Threads) void k_down2(
         for (int u = 0; u < U; ++u) {  // loads that depend on the slot number only
             const int jc = min((r0 + u * kDown2RowsPerLoad + rslot) * P + g, ffn - 1);
             iv[u] = idx[jc];
-#pragma unroll
-            for (int b = 0; b < B; ++b) hv[u][b] = h[(size_t)b * ffn + jc];
+            load_h_slot<B>(h, jc, hv[u]);
         }
         if (!have_n) {
             n = min(max(*count_p, 0), ffn);

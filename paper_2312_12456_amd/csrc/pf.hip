@@ -49,7 +49,7 @@ struct pf_ctx {
     uint64_t *mask_words = nullptr;  // [max_ffn / 64]
     int32_t *idx = nullptr;          // [max_ffn]
     int32_t *count = nullptr;        // [1]
-    float *h = nullptr;              // [max_batch][max_ffn] FC1 outputs of the listed neurons
+    float *h = nullptr;              // [max_ffn][h_stride(batch)] FC1 outputs, by list slot
     float *ypart = nullptr;          // [4][max_batch][max_d] FC2 output as partial sums
     float *xbuf[2] = {nullptr, nullptr};  // [max_batch][max_d] layer inputs inside pf_stack_step
     hipStream_t capture_stream = nullptr;
@@ -327,13 +327,13 @@ pf_status launch_sparse_i4(pf_ctx *ctx, const pf_layer *L, const float *x, int B
         const int bt = (B - b0) < tile ? (B - b0) : tile;
         const size_t lds = (size_t)bt * per_tok + pf::kStageScrap * sizeof(float) + extra;
         const float *xb = x + (size_t)b0 * D.d;
-        float *hb = ctx->h + (size_t)b0 * D.ffn;
+        float *hb = ctx->h + b0;
         ProfScope ps(ctx, K_UP);
 #define PF_UP4(ACT, FM)                                                                           \
     PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_up_i4<BT, ACT, FM>), dim3(up_grid),                      \
                               dim3(pf::kUpI4Threads), lds, st, q_up, s_up, q_gate, s_gate,        \
                               L->w.b_up, xb, idx_in, count_in, mask_words, ctx->idx, ctx->count,  \
-                              hb, D.d, D.ffn))
+                              hb, pf::h_stride(B), D.d, D.ffn))
         if (gated && from_mask) { PF_UP4(1, true); }
         else if (gated) { PF_UP4(1, false); }
         else if (from_mask) { PF_UP4(0, true); }
@@ -393,7 +393,7 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
 #define PF_UPM(ACT, FM)                                                                           \
     PF_LAUNCH(ps, (pf::k_up_mfma<ACT, FM>), dim3(grid), dim3(pf::kMfmaThreads), mfma_lds, st, w_up, \
               w_gate, L->w.b_up, x, B, idx_in, count_in, mask_words, ctx->idx, ctx->count, ctx->h, \
-              D.d, D.ffn)
+              pf::h_stride(B), D.d, D.ffn)
         if (gated && from_mask) { PF_UPM(1, true); }
         else if (gated) { PF_UPM(1, false); }
         else if (from_mask) { PF_UPM(0, true); }
@@ -404,13 +404,13 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
         const int bt = (B - b0) < tile ? (B - b0) : tile;
         const size_t lds = ((size_t)bt * kpad_of(D.d) + pf::kStageScrap) * sizeof(float) + extra;
         const float *xb = x + (size_t)b0 * D.d;
-        float *hb = ctx->h + (size_t)b0 * D.ffn;
+        float *hb = ctx->h + b0;
         ProfScope ps(ctx, K_UP);
 #define PF_UP(ACT, FM)                                                                            \
     PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_up<BT, ACT, FM>), dim3(up_grid),                    \
                                        dim3(pf::kUpThreads), lds, st, w_up, w_gate, L->w.b_up, xb, \
                                        idx_in, count_in, mask_words, ctx->idx, ctx->count, hb,    \
-                                       D.d, D.ffn))
+                                       pf::h_stride(B), D.d, D.ffn))
         if (gated && from_mask) { PF_UP(1, true); }
         else if (gated) { PF_UP(1, false); }
         else if (from_mask) { PF_UP(0, true); }
@@ -576,7 +576,7 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         PF_ALLOC(ctx->mask_words, (size_t)(max_ffn / 64) * sizeof(uint64_t));
         PF_ALLOC(ctx->idx, (size_t)max_ffn * sizeof(int32_t));
         PF_ALLOC(ctx->count, 64);
-        PF_ALLOC(ctx->h, (size_t)max_batch * max_ffn * sizeof(float));
+        PF_ALLOC(ctx->h, (size_t)pf::h_stride(max_batch) * max_ffn * sizeof(float));
         PF_ALLOC(ctx->ypart, (size_t)pf::kDown2MaxSplit * max_batch * max_d * sizeof(float));
         PF_ALLOC(ctx->xbuf[0], (size_t)max_batch * max_d * sizeof(float));
         PF_ALLOC(ctx->xbuf[1], (size_t)max_batch * max_d * sizeof(float));
