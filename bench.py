@@ -39,7 +39,11 @@ def parse_args():
     ap.add_argument("--config", default="opt-6.7b")
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--layers", type=int, default=None, help="override the layer count")
-    ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
+    ap.add_argument("--mode", choices=["graph", "eager", "copycal"], default="graph",
+                    help="copycal: only run plain device copies of a known size, to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters by")
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "pmc_traffic.json"),
+                    help="HBM bytes per launch per kernel from the rocprofv3 --pmc runs (optional)")
     ap.add_argument("--profile-steps", type=int, default=16)
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--cpu-layers", type=int, default=2)
@@ -67,6 +71,17 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.mode == "copycal":
+        # 16 copies of 256 MiB: each dispatch reads 2^28 and writes 2^28 bytes
+        src = torch.empty(1 << 26, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(16):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "copycal", "copies": 16, "bytes_read_per_copy": src.numel() * 4,
+                          "bytes_written_per_copy": src.numel() * 4}))
+        return
     cfg = wl.CONFIGS[args.config]
     if args.layers:
         cfg = wl.scaled(cfg, layers=args.layers)
@@ -148,9 +163,20 @@ def main():
         kernels[name] = ent
     dominant = max((n for n in kernels if n in alg_bytes), key=lambda n: stats[n][1])
     dk = kernels[dominant]
+    # measured HBM traffic of that kernel per launch, if the counter runs were summarised for
+    # this workload (profiles/: FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size)
+    traffic = None
+    try:
+        with open(args.traffic_file) as f:
+            tf = json.load(f)
+        key = "%s/b%d" % (cfg.name, B)
+        if key in tf and dominant in tf[key]:
+            traffic = tf[key][dominant]["hbm_bytes_per_launch"]
+    except (OSError, ValueError, KeyError):
+        traffic = None
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": dk["GBps"], "peak": HBM_PEAK_GBPS,
-        "unit": "GB/s", "frac": round(dk["GBps"] / HBM_PEAK_GBPS, 4), "traffic": None,
+        "unit": "GB/s", "frac": round(dk["GBps"] / HBM_PEAK_GBPS, 4), "traffic": traffic,
         "alg_bytes_per_launch": dk["alg_bytes"], "avg_us": dk["avg_us"],
     }
     touched = k_mean * nm * cfg.row_bytes
