@@ -252,52 +252,55 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
 
 // ---------------------------------------------------------------------------------------
 // The predictor's two layers for a batch on the matrix cores (PowerInfer Sec. 5.1): dense
-// rows, so no list and no row gather.  Block b owns rows [16 T b, 16 T (b + 1)); its 8 waves
-// take the chunks of KC elements of the row length K round-robin, each through its own LDS
-// slot of 16 T rows x KC halfs filled by global -> LDS loads that read 2 KC bytes of each of
-// 512 / KC rows per instruction (whole lines).  Row R keeps 16-byte piece p at position
-// p ^ (R & 7): the 8 rows a group of 8 lanes reads together (same piece) then fall into 8
+// rows, so no list and no row gather.  Block b owns rows [R b, R (b + 1)); its 8 waves take
+// the chunks of KC elements of the row length K round-robin, each through its own 8 KB LDS
+// slot of R rows x KC halfs filled by global -> LDS loads that read 2 KC bytes of each of
+// 512 / KC rows per instruction (whole lines).  Row r keeps 16-byte piece p at position
+// p ^ (r & 7): the 8 rows a group of 8 lanes reads together (same piece) then fall into 8
 // different bank groups.  v[B][K] are the activations (fp32, split into fp16 hi + lo).
-//   EPI 0 (hidden layer, T = 1): out[b][row] = ReLU(sum)                       out = t
-//   EPI 1 (output layer, T = 4): logit = sum + p_bias[row]; scores[b][row] = sigmoid(logit)
-//         if asked; bit `row` of the mask word of block b = any_b(logit > thr)
-constexpr int kRowsMfmaSlotBytes = 8192;  // 16 T rows x 2 KC bytes for both shapes in use
+//   EPI 0 (hidden layer, R = 8, KC = 512: few rows, so few and long chunks; rows 8..15 of
+//          the MFMA tile are zeros):               out[b][row] = ReLU(sum)          out = t
+//   EPI 1 (output layer, R = 64 = one mask word, KC = 64): logit = sum + p_bias[row];
+//          scores[b][row] = sigmoid(logit) if asked; bit `row` of mask word b = any_b(logit > thr)
+constexpr int kRowsMfmaSlotBytes = 8192;  // R rows x 2 KC bytes
 
-template <int T, int KC>
+template <int R, int KC>
 __device__ __forceinline__ void rows_mfma_issue(rsrc_t w, char *slot, uint32_t row0_off, uint32_t row_bytes,
                                                 int nrows_left, int c, int K, int lane)
 {
-    constexpr int RPI = 512 / KC;       // rows per instruction
-    constexpr int LPR = 64 / RPI;       // lanes (16-byte pieces) per row
-    constexpr int NI = 16 * T / RPI;    // instructions per chunk
+    constexpr int RPI = 512 / KC;  // rows per instruction
+    constexpr int LPR = 64 / RPI;  // lanes (16-byte pieces) per row
+    constexpr int NI = R / RPI;    // instructions per chunk
     const int rin = lane / LPR, p = lane % LPR;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-        const int R = RPI * i + rin;
-        const int piece = p ^ (R & 7);
+        const int row = RPI * i + rin;
+        const int piece = p ^ (row & 7);
         const int k = c * KC + piece * 8;
-        const uint32_t off = (k < K && R < nrows_left) ? row0_off + (uint32_t)R * row_bytes + (uint32_t)k * 2u
-                                                       : kOobOffset;
+        const uint32_t off = (k < K && row < nrows_left) ? row0_off + (uint32_t)row * row_bytes + (uint32_t)k * 2u
+                                                         : kOobOffset;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(w, (lds_ptr_t)(slot + i * 1024), 16, (int)off, 0, 0, 0);
     }
 }
 
-template <int T, int KC, int EPI>
+template <int R, int KC, int EPI>
 __global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
     const __half *__restrict__ w, const float *__restrict__ v, int B, int K, int nrows,
     const float *__restrict__ p_bias, float thr_logit, float *__restrict__ out,
     uint64_t *__restrict__ mask_words)
 {
     extern __shared__ uint64_t dyn_lds64[];
+    constexpr int T = (R + 15) / 16;  // MFMA tiles per block
     __shared__ float logit_s[16][16 * T];
-    static_assert(16 * T * KC * 2 == kRowsMfmaSlotBytes, "slot size");
-    static_assert(EPI == 0 || T == 4, "the output layer writes one mask word per block");
-    constexpr int STEPS = KC / 32;
+    static_assert(R * KC * 2 == kRowsMfmaSlotBytes, "slot size");
+    static_assert(EPI == 0 || R == 64, "the output layer writes one mask word per block");
+    constexpr int STEPS = KC / 32;                // MFMA K steps per chunk
+    constexpr int SB = STEPS < 4 ? STEPS : 4;     // ... of which this many share a round of loads
     const int lane = threadIdx.x & 63, wave = wave_uniform(threadIdx.x >> 6);
     const int row16 = lane & 15, kg = lane >> 4;
     char *slots = reinterpret_cast<char *>(dyn_lds64);
     char *slot = slots + (size_t)wave * kRowsMfmaSlotBytes;
-    const int r0 = blockIdx.x * 16 * T;
+    const int r0 = blockIdx.x * R;
     const int nleft = nrows - r0;  // rows of this block that exist (>= 1)
     const rsrc_t wr = make_rsrc(w, (uint32_t)nrows * (uint32_t)K * 2u);
     const rsrc_t vr = make_rsrc(v, (uint32_t)B * (uint32_t)K * 4u);
@@ -305,45 +308,73 @@ __global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
     const uint32_t voff = row16 < B ? ((uint32_t)row16 * (uint32_t)K + (uint32_t)kg * 8u) * 4u : kOobOffset;
     const int nchunks = (K + KC - 1) / KC;
 
+    PF_TSTAMP(EPI, 0);
     float4v_t acc[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) acc[t] = (float4v_t){0.f, 0.f, 0.f, 0.f};
-    int c = wave;
-    if (c < nchunks) rows_mfma_issue<T, KC>(wr, slot, row0_off, row_bytes, nleft, c, K, lane);
-    while (c < nchunks) {  // wave-uniform
-        float4 xa[STEPS], xb[STEPS];
+    // activations of sub-block j (SB K steps) of chunk ch into one of two register buffers: they
+    // are fetched one sub-block ahead of their use, so that their L2 round trip overlaps the
+    // matrix work of the sub-block before
+    constexpr int NSB = STEPS / SB;
+    float4 xa[2][SB], xb[2][SB];
+    auto load_x = [&](int ch, int j, float4 (&pa)[SB], float4 (&pb)[SB]) {
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            const int k = c * KC + s * 32;
+        for (int s = 0; s < SB; ++s) {
+            const int k = ch * KC + (j * SB + s) * 32;
             const uint32_t o = (k < K && voff != kOobOffset) ? voff + (uint32_t)k * 4u : kOobOffset;
-            xa[s] = ld16_f32(vr, o);
-            xb[s] = ld16_f32(vr, o != kOobOffset ? o + 16u : kOobOffset);
+            pa[s] = ld16_f32(vr, o);
+            pb[s] = ld16_f32(vr, o != kOobOffset ? o + 16u : kOobOffset);
         }
-        Half8Bits a[T][STEPS];
-#pragma unroll
-        for (int t = 0; t < T; ++t)
-#pragma unroll
-            for (int s = 0; s < STEPS; ++s) {
-                const int R = 16 * t + row16;
-                a[t][s].u = *reinterpret_cast<const uint4 *>(slot + R * (KC * 2) + ((4 * s + kg) ^ (R & 7)) * 16);
-            }
+    };
+    int c = wave;
+    if (c < nchunks) {
+        rows_mfma_issue<R, KC>(wr, slot, row0_off, row_bytes, nleft, c, K, lane);
+        load_x(c, 0, xa[0], xb[0]);
+    }
+    while (c < nchunks) {  // wave-uniform
         const int cn = c + kMfmaWaves;
-        if (cn < nchunks) {  // refill the slot once its contents are in the registers
-            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-            rows_mfma_issue<T, KC>(wr, slot, row0_off, row_bytes, nleft, cn, K, lane);
+#pragma unroll
+        for (int j = 0; j < NSB; ++j) {
+            const int cur = j & 1, nxt = cur ^ 1;
+            Half8Bits a[T][SB];
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int s = 0; s < SB; ++s) {
+                    const int row = 16 * t + row16;
+                    a[t][s].u = make_uint4(0u, 0u, 0u, 0u);
+                    if (R >= 16 || row < R)
+                        a[t][s].u = *reinterpret_cast<const uint4 *>(
+                            slot + row * (KC * 2) + ((4 * (j * SB + s) + kg) ^ (row & 7)) * 16);
+                }
+            if (j + 1 < NSB) {
+                load_x(c, j + 1, xa[nxt], xb[nxt]);
+            } else if (cn < nchunks) {  // last sub-block: refill the slot, fetch the next chunk's x
+                __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the slot is all in registers
+                rows_mfma_issue<R, KC>(wr, slot, row0_off, row_bytes, nleft, cn, K, lane);
+                load_x(cn, 0, xa[nxt], xb[nxt]);
+            }
+#pragma unroll
+            for (int s = 0; s < SB; ++s) {
+                half8_t hi, lo;
+                split_hi_lo(xa[cur][s], xb[cur][s], hi, lo);
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[t][s].h, hi, acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[t][s].h, lo, acc[t], 0, 0, 0);
+                }
+            }
         }
+        if (NSB & 1) {  // the next chunk starts from buffer 0 again
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            half8_t hi, lo;
-            split_hi_lo(xa[s], xb[s], hi, lo);
-#pragma unroll
-            for (int t = 0; t < T; ++t) {
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[t][s].h, hi, acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[t][s].h, lo, acc[t], 0, 0, 0);
+            for (int s = 0; s < SB; ++s) {
+                xa[0][s] = xa[1][s];
+                xb[0][s] = xb[1][s];
             }
         }
         c = cn;
     }
+    PF_TSTAMP(EPI, 1);
     // this lane holds C[tile t][row 4*kg + e][col row16] of its chunks; the slot is free now
     float *ctile = reinterpret_cast<float *>(slot);
 #pragma unroll
@@ -358,7 +389,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
         for (int wv = 0; wv < kMfmaWaves; ++wv)
             sum += reinterpret_cast<const float *>(slots + (size_t)wv * kRowsMfmaSlotBytes)[e];
         if (EPI == 0) {
-            if (col < B && row < nleft) out[(size_t)col * nrows + r0 + row] = fmaxf(sum, 0.f);
+            if (col < B && row < R && row < nleft) out[(size_t)col * nrows + r0 + row] = fmaxf(sum, 0.f);
         } else {
             const float lg = sum + (p_bias ? p_bias[r0 + row] : 0.f);
             logit_s[col][row] = lg;
@@ -374,6 +405,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
             if (lane == 0) mask_words[blockIdx.x] = word;
         }
     }
+    PF_TSTAMP(EPI, 2);
 }
 
 }  // namespace pf

@@ -277,8 +277,58 @@ constexpr int kGlueThreads = 1024;
 
 // x_next may alias x: every element is read and written by the same thread.
 // y may come as ny partial sums [ny][B][d] (see k_down2): they are added in order.
+// d <= kGlueMaxD: a thread keeps its (up to 4) float4 sums in registers, so every load of the
+// kernel is issued before the first one is waited for -- one round trip, then the block
+// reduction, then the stores.
+constexpr int kGlueMaxD = kGlueThreads * 4 * 4;
+
 __global__ __launch_bounds__(kGlueThreads) void k_glue(const float *x, const float *__restrict__ y,
                                                        int ny, float *x_next, int d)
+{
+    __shared__ float wsum[kGlueThreads / kWave];
+    const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t pbytes = (uint32_t)gridDim.x * (uint32_t)d * 4u;  // between partial sums
+    const rsrc_t xr = make_rsrc(x + (size_t)b * d, (uint32_t)d * 4u);
+    const rsrc_t yr = make_rsrc(y + (size_t)b * d, (uint32_t)(ny - 1) * pbytes + (uint32_t)d * 4u);
+    float4 v[4], p[4][kGlueMaxParts];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = (i * kGlueThreads + (int)threadIdx.x) * 4;
+        const uint32_t off = e < d ? (uint32_t)e * 4u : kOobOffset;
+        v[i] = ld16_f32(xr, off);
+#pragma unroll
+        for (int q = 0; q < kGlueMaxParts; ++q)
+            p[i][q] = ld16_f32(yr, (e < d && q < ny) ? off + (uint32_t)q * pbytes : kOobOffset);
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float4 t = p[i][0];
+#pragma unroll
+        for (int q = 1; q < kGlueMaxParts; ++q)
+            t = make_float4(t.x + p[i][q].x, t.y + p[i][q].y, t.z + p[i][q].z, t.w + p[i][q].w);
+        v[i] = make_float4(v[i].x + t.x, v[i].y + t.y, v[i].z + t.z, v[i].w + t.w);
+        ss = fmaf(v[i].x, v[i].x, fmaf(v[i].y, v[i].y, fmaf(v[i].z, v[i].z, fmaf(v[i].w, v[i].w, ss))));
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) wsum[wave] = ss;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int k = 0; k < kGlueThreads / kWave; ++k) tot += wsum[k];
+    const float scale = tot > 0.f ? sqrtf((float)d / tot) : 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = (i * kGlueThreads + (int)threadIdx.x) * 4;
+        if (e < d)
+            *reinterpret_cast<float4 *>(x_next + (size_t)b * d + e) =
+                make_float4(v[i].x * scale, v[i].y * scale, v[i].z * scale, v[i].w * scale);
+    }
+}
+
+// The same for any d (two passes over the inputs).
+__global__ __launch_bounds__(kGlueThreads) void k_glue_long(const float *x, const float *__restrict__ y,
+                                                            int ny, float *x_next, int d)
 {
     __shared__ float wsum[kGlueThreads / kWave];
     const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;

@@ -154,8 +154,8 @@ hipError_t allow_lds_mfma()
     if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<0, true>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, false>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, true>);
-    if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<1, 256, 0>);
-    if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<4, 64, 1>);
+    if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<8, 512, 0>);
+    if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<64, 64, 1>);
     return e;
 }
 
@@ -239,7 +239,7 @@ pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const fl
             x = x_new;
         }
         ProfScope ps(ctx, K_PRED_HIDDEN);
-        PF_LAUNCH(ps, (pf::k_rows_mfma<1, 256, 0>), dim3(cdiv(D.r, 16)), dim3(pf::kMfmaThreads),
+        PF_LAUNCH(ps, (pf::k_rows_mfma<8, 512, 0>), dim3(cdiv(D.r, 8)), dim3(pf::kMfmaThreads),
                   (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p1, x, B, D.d, D.r,
                   (const float *)nullptr, 0.f, ctx->t, (uint64_t *)nullptr);
         PF_HIP(ctx, hipGetLastError());
@@ -280,7 +280,7 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
     const __half *p2 = static_cast<const __half *>(L->w.p2);
     if (pred_mfma(ctx, D.r, B)) {
         ProfScope ps(ctx, K_PRED_OUT);
-        PF_LAUNCH(ps, (pf::k_rows_mfma<4, 64, 1>), dim3(D.ffn / 64), dim3(pf::kMfmaThreads),
+        PF_LAUNCH(ps, (pf::k_rows_mfma<64, 64, 1>), dim3(D.ffn / 64), dim3(pf::kMfmaThreads),
                   (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p2, (const float *)ctx->t, B, D.r,
                   D.ffn, L->w.p_bias, L->thr_logit, scores, mask_words);
         PF_HIP(ctx, hipGetLastError());
@@ -459,7 +459,10 @@ pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int ny, int d
 {
     {
         ProfScope ps(ctx, K_GLUE);
-        PF_LAUNCH(ps, pf::k_glue, dim3(B), dim3(pf::kGlueThreads), 0, st, x, y, ny, x_next, d);
+        if (d <= pf::kGlueMaxD && d % 4 == 0)
+            PF_LAUNCH(ps, pf::k_glue, dim3(B), dim3(pf::kGlueThreads), 0, st, x, y, ny, x_next, d);
+        else
+            PF_LAUNCH(ps, pf::k_glue_long, dim3(B), dim3(pf::kGlueThreads), 0, st, x, y, ny, x_next, d);
     }
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
