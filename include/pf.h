@@ -115,7 +115,8 @@ pf_status pf_compact(pf_ctx *ctx, const uint64_t *mask_words, int ffn, int32_t *
  *   y[b][:] = b_down + sum_j h_j[b] * (row i of FC2^T)
  * for every token b of the batch (the list is the union over the batch, Sec. 8.2).
  * idx: ascending, no duplicates, entries in [0, ffn) (out-of-range entries are skipped);
- * count: device int32, clamped to [0, ffn].  y [B][d] fp32 is fully overwritten, also
+ * the array must hold ffn entries whatever *count is (entries from *count on may be read
+ * ahead of the count and are ignored).  count: device int32, clamped to [0, ffn].  y [B][d] fp32 is fully overwritten, also
  * when *count == 0 (then y = b_down).  Accumulation is fp32, in a fixed order. */
 pf_status pf_sparse_ffn(pf_ctx *ctx, const pf_layer *layer, const float *x, int B,
                         const int32_t *idx, const int32_t *count, float *y, void *stream);
