@@ -39,9 +39,12 @@ def parse_args():
     ap.add_argument("--config", default="opt-6.7b")
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--layers", type=int, default=None, help="override the layer count")
-    ap.add_argument("--mode", choices=["graph", "eager", "copycal"], default="graph",
+    ap.add_argument("--mode", choices=["graph", "eager", "copycal", "m0"], default="graph",
                     help="copycal: only run plain device copies of a known size, to scale "
-                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters by")
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters by; m0: operator "
+                         "micro-benchmark, one 4096 x 4096 layer, active fraction swept")
+    ap.add_argument("--rate", type=float, default=None,
+                    help="override the configuration's mean activation rate (scaling runs)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "pmc_traffic.json"),
                     help="HBM bytes per launch per kernel from the rocprofv3 --pmc runs (optional)")
     ap.add_argument("--profile-steps", type=int, default=16)
@@ -52,6 +55,41 @@ def parse_args():
                     help="bias-free random predictor (about half of the neurons marked)")
     ap.add_argument("--seed", type=int, default=2312)
     return ap.parse_args()
+
+
+def operator_microbench(args, torch, np, pf, wl):
+    """The paper's operator test (Sec. 8.3.2 'neuron-aware operators'): one FFN layer with
+    4096 x 4096 matrices, batch 1, a uniformly random set of active rows of swept size; time
+    of FC1 and FC2 against the active fraction (slope = 1 / bandwidth, intercept = latency)."""
+    cfg = wl.scaled(wl.CONFIGS["opt-6.7b"], name="m0-4096x4096", layers=1, ffn=4096, r=128)
+    ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=1)
+    lay = wl.make_layer(cfg, 0, args.seed, device="cuda")
+    L = pf.Layer.from_workload(ctx, cfg, lay)
+    x = wl.make_inputs(cfg, 0, args.seed, batch=1, device="cuda")
+    y = torch.empty_like(x)
+    rng = np.random.Generator(np.random.PCG64(args.seed))
+    rows = []
+    for frac in (0.01, 0.02, 0.05, 0.1, 0.2, 0.5, 1.0):
+        k = max(1, int(round(frac * cfg.ffn)))
+        sel = np.sort(rng.choice(cfg.ffn, size=k, replace=False)).astype(np.int32)
+        idx = torch.zeros(cfg.ffn, dtype=torch.int32, device="cuda")
+        idx[:k] = torch.from_numpy(sel).cuda()
+        cnt = torch.tensor([k], dtype=torch.int32, device="cuda")
+        for _ in range(8):
+            ctx.sparse_ffn(L, x, idx, cnt, y)
+        torch.cuda.synchronize()
+        ctx.profile_begin()
+        for _ in range(64):
+            ctx.sparse_ffn(L, x, idx, cnt, y)
+        st = ctx.profile_end()
+        up_us = 1e3 * st["k_up"][1] / st["k_up"][0]
+        dn_us = 1e3 * st["k_down"][1] / st["k_down"][0]
+        by = k * cfg.row_bytes
+        rows.append({"fraction": frac, "k": k, "bytes_per_matrix": by, "fc1_us": round(up_us, 3),
+                     "fc2_us": round(dn_us, 3), "fc1_GBps": round(by / up_us / 1e3, 1),
+                     "fc2_GBps": round(by / dn_us / 1e3, 1)})
+    return {"mode": "m0", "workload": "one layer, d=4096, ffn=4096, fp16, batch 1, uniformly "
+            "random active rows, 64 launches per point", "points": rows}
 
 
 def main():
@@ -82,9 +120,14 @@ def main():
         print(json.dumps({"mode": "copycal", "copies": 16, "bytes_read_per_copy": src.numel() * 4,
                           "bytes_written_per_copy": src.numel() * 4}))
         return
+    if args.mode == "m0":
+        print(json.dumps(operator_microbench(args, torch, np, pf, wl)))
+        return
     cfg = wl.CONFIGS[args.config]
     if args.layers:
         cfg = wl.scaled(cfg, layers=args.layers)
+    if args.rate is not None:
+        cfg = wl.scaled(cfg, rate=args.rate)
     B = args.batch
     K = args.steps if args.steps is not None else cfg.tokens
     W = args.warmup
@@ -125,6 +168,18 @@ def main():
     assert bool(torch.isfinite(out).all()), "non-finite stack output"
     ms_per_step = 1e3 * elapsed / K
     tokens_per_s = B * K / elapsed
+
+    # per-token latency spread: a second, short run with an event between the steps
+    nl = min(K, 128)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(nl + 1)]
+    evs[0].record()
+    for t in range(nl):
+        step(t)
+        evs[t + 1].record()
+    torch.cuda.synchronize()
+    lat = np.array([evs[t].elapsed_time(evs[t + 1]) for t in range(nl)])
+    latency = {"steps": nl, "p50_ms": round(float(np.percentile(lat, 50)), 4),
+               "p95_ms": round(float(np.percentile(lat, 95)), 4), "max_ms": round(float(lat.max()), 4)}
 
     # ---- per-kernel pass: HIP events around every launch, active counts read back ----
     P = max(1, min(args.profile_steps, n_tok))
@@ -236,6 +291,7 @@ def main():
         "touched": {"k_mean": round(k_mean, 1), "active_frac": round(k_mean / cfg.ffn, 4),
                     "bytes_per_layer": touched, "sparse_us_per_layer": round(t_sparse_us, 3),
                     "GBps": round(touched_gbps, 1), "frac_of_peak": round(touched_gbps / HBM_PEAK_GBPS, 4)},
+        "latency": latency,
         "kernels": kernels,
         "setup_s": round(t_gen, 1),
     }
