@@ -43,6 +43,9 @@ def parse_args():
                     help="copycal: only run plain device copies of a known size, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters by; m0: operator "
                          "micro-benchmark, one 4096 x 4096 layer, active fraction swept")
+    ap.add_argument("--sort-neurons", type=int, default=0, metavar="N",
+                    help="profile activation counts over N tokens first and lay every layer's "
+                         "neurons out hot-first (frequency-sorted layout)")
     ap.add_argument("--rate", type=float, default=None,
                     help="override the configuration's mean activation rate (scaling runs)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "pmc_traffic.json"),
@@ -147,6 +150,24 @@ def main():
     out = torch.empty((B, cfg.d), device=dev)
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
+
+    if args.sort_neurons > 0:
+        # activation profiler -> neuron table -> hot-first layout (the caller owns the weights,
+        # so the re-layout is the caller's: here, the harness's)
+        tabs = [torch.zeros(cfg.ffn, dtype=torch.int32, device=dev) for _ in range(cfg.layers)]
+        xa0, y0 = torch.empty((B, cfg.d), device=dev), torch.empty((B, cfg.d), device=dev)
+        for t in range(min(args.sort_neurons, n_tok)):
+            xa0.copy_(x_all[t])
+            for l, L in enumerate(layers):
+                ctx.layer_step(L, xa0, y0)
+                ctx.count_activations(L, tabs[l])
+                ctx.stack_glue(xa0, y0, xa0)
+        torch.cuda.synchronize()
+        for l in range(cfg.layers):
+            order = torch.argsort(tabs[l], descending=True, stable=True).cpu().numpy()
+            tensors[l] = wl.permute_neurons(tensors[l], order)
+            layers[l] = pf.Layer.from_workload(ctx, cfg, tensors[l])
+        torch.cuda.synchronize()
 
     plan = pf.Plan(ctx, layers, x_buf, out) if args.mode == "graph" else None
 
@@ -285,7 +306,9 @@ def main():
                                   "ReGLU" if cfg.act == wl.ACT_REGLU else "ReLU",
                                   "int4-g128" if cfg.wtype == wl.W_INT4_G128 else "fp16",
                                   B, cfg.alpha, 100 * cfg.rate, K),
-                   "launch": args.mode, "predictor_bias": not args.no_pred_bias},
+                   "launch": args.mode, "predictor_bias": not args.no_pred_bias,
+                   "neuron_layout": ("hot-first from %d profiled tokens" % args.sort_neurons)
+                   if args.sort_neurons > 0 else "as generated"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "touched": {"k_mean": round(k_mean, 1), "active_frac": round(k_mean / cfg.ffn, 4),

@@ -126,9 +126,33 @@ pf_status pf_sparse_ffn(pf_ctx *ctx, const pf_layer *layer, const float *x, int 
 pf_status pf_layer_step(pf_ctx *ctx, const pf_layer *layer, const float *x, int B, float *y,
                         void *stream);
 
-/* Device pointers to the mask words, index list and count left by the last
- * pf_layer_step on this context (valid until the next compute call; for tests and
- * for an activation profiler in the sense of Sec. 6.1). */
+/* Dense FFN of the layer: every neuron is computed and the predictor is not used
+ * (Sec. 8.2: dense computation when the joint activation of a long prompt or a large batch
+ * covers nearly all neurons).  Equal to pf_sparse_ffn over the list 0 .. ffn-1.
+ * x [B][d] -> y [B][d]; the layer needs no predictor weights. */
+pf_status pf_dense_ffn(pf_ctx *ctx, const pf_layer *layer, const float *x, int B, float *y,
+                       void *stream);
+
+/* Layer step with the dense fallback of Sec. 8.2: when density_hint -- the caller's
+ * expectation of count / ffn for this step, e.g. the previous step's, or 1 for a long
+ * prompt -- is at least crossover (a fraction in (0, 1]), the dense path runs and the
+ * predictor is skipped; otherwise this is pf_layer_step.  The decision is taken on the host
+ * before anything is launched: once the predictor has run its cost is sunk, and the sparse
+ * kernels are then never slower than the dense ones.  Returns PF_EINVAL for a crossover
+ * outside (0, 1] or a negative hint. */
+pf_status pf_layer_step_auto(pf_ctx *ctx, const pf_layer *layer, const float *x, int B,
+                             float density_hint, float crossover, float *y, void *stream);
+
+/* Activation profiler (the counting of Sec. 6.1 that fills the neuron table): counts[i] += 1
+ * for every neuron i of the list the context used last (pf_layer_step, pf_layer_step_auto,
+ * pf_dense_ffn; not pf_sparse_ffn, whose list is the caller's).  counts: [ffn] uint32 on the
+ * device, caller-owned, zeroed by the caller before the first call.  One launch on `stream`,
+ * no host synchronisation; the list holds no duplicates, so no atomics are involved. */
+pf_status pf_count_activations(pf_ctx *ctx, const pf_layer *layer, uint32_t *counts, void *stream);
+
+/* Device pointers to the mask words, index list and count left by the last layer step on
+ * this context (valid until the next compute call).  After a dense step idx / count are the
+ * full list and *mask_words is NULL. */
 pf_status pf_ctx_last_active(pf_ctx *ctx, const uint64_t **mask_words, const int32_t **idx,
                              const int32_t **count);
 

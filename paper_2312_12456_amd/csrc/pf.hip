@@ -49,6 +49,10 @@ struct pf_ctx {
     uint64_t *mask_words = nullptr;  // [max_ffn / 64]
     int32_t *idx = nullptr;          // [max_ffn]
     int32_t *count = nullptr;        // [1]
+    int32_t *idx_all = nullptr;      // [max_ffn] 0, 1, 2, ...: the list of the dense path
+    int32_t *count_all = nullptr;    // [1] = max_ffn (kernels clamp the count to the layer's ffn)
+    const uint64_t *last_mask = nullptr;  // what the last layer step used
+    const int32_t *last_idx = nullptr, *last_count = nullptr;
     float *h = nullptr;              // [max_ffn][h_stride(batch)] FC1 outputs, by list slot
     float *ypart = nullptr;          // [4][max_batch][max_d] FC2 output as partial sums
     float *xbuf[2] = {nullptr, nullptr};  // [max_batch][max_d] layer inputs inside pf_stack_step
@@ -451,6 +455,9 @@ pf_status launch_layer(pf_ctx *ctx, const pf_layer *L, const float *x, const flo
     const float *x_in = glue_y ? x_new : x;
     pf_status s = launch_predict(ctx, L, x, glue_y, glue_ny, x_new, B, nullptr, ctx->mask_words, st);
     if (s != PF_OK) return s;
+    ctx->last_mask = ctx->mask_words;
+    ctx->last_idx = ctx->idx;
+    ctx->last_count = ctx->count;
     return launch_sparse(ctx, L, x_in, B, nullptr, nullptr, ctx->mask_words, y, ny_out, st);
 }
 
@@ -506,6 +513,24 @@ pf_status check_stack(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const 
         if (!layers[l]->w.p1) return fail(ctx, PF_EINVAL, "layer %d has no predictor", l);
     }
     return PF_OK;
+}
+
+__global__ void k_iota(int32_t *idx, int n, int32_t *count)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) idx[i] = i;
+    if (i == 0) *count = n;
+}
+
+// counts[idx[j]] += 1 for j < *count: every neuron is listed at most once
+__global__ void k_count_activations(const int32_t *__restrict__ idx, const int32_t *__restrict__ count_p,
+                                    int ffn, uint32_t *__restrict__ counts)
+{
+    const int n = min(max(*count_p, 0), ffn);
+    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < n; j += gridDim.x * blockDim.x) {
+        const int i = idx[j];
+        if ((unsigned)i < (unsigned)ffn) counts[i] += 1u;
+    }
 }
 
 }  // namespace
@@ -579,12 +604,20 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         PF_ALLOC(ctx->mask_words, (size_t)(max_ffn / 64) * sizeof(uint64_t));
         PF_ALLOC(ctx->idx, (size_t)max_ffn * sizeof(int32_t));
         PF_ALLOC(ctx->count, 64);
+        PF_ALLOC(ctx->idx_all, (size_t)max_ffn * sizeof(int32_t));
+        PF_ALLOC(ctx->count_all, 64);
         PF_ALLOC(ctx->h, (size_t)pf::h_stride(max_batch) * max_ffn * sizeof(float));
         PF_ALLOC(ctx->ypart, (size_t)pf::kDown2MaxSplit * max_batch * max_d * sizeof(float));
         PF_ALLOC(ctx->xbuf[0], (size_t)max_batch * max_d * sizeof(float));
         PF_ALLOC(ctx->xbuf[1], (size_t)max_batch * max_d * sizeof(float));
 #undef PF_ALLOC
         e = hipMemset(ctx->count, 0, 64);
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(k_iota, dim3(cdiv(max_ffn, 256)), dim3(256), 0, 0, ctx->idx_all, max_ffn,
+                               ctx->count_all);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->capture_stream, hipStreamNonBlocking);
         if (e != hipSuccess) { st = PF_EHIP; break; }
     } while (0);
@@ -606,6 +639,8 @@ void pf_ctx_destroy(pf_ctx *ctx)
     (void)hipFree(ctx->mask_words);
     (void)hipFree(ctx->idx);
     (void)hipFree(ctx->count);
+    (void)hipFree(ctx->idx_all);
+    (void)hipFree(ctx->count_all);
     (void)hipFree(ctx->h);
     (void)hipFree(ctx->ypart);
     (void)hipFree(ctx->xbuf[0]);
@@ -707,13 +742,49 @@ pf_status pf_layer_step(pf_ctx *ctx, const pf_layer *layer, const float *x, int 
                         static_cast<hipStream_t>(stream));
 }
 
+pf_status pf_dense_ffn(pf_ctx *ctx, const pf_layer *layer, const float *x, int B, float *y,
+                       void *stream)
+{
+    pf_status s = check_batch(ctx, layer, x, B);
+    if (s != PF_OK) return s;
+    if (!y) return fail(ctx, PF_EINVAL, "y is null");
+    ctx->last_mask = nullptr;
+    ctx->last_idx = ctx->idx_all;
+    ctx->last_count = ctx->count_all;
+    return launch_sparse(ctx, layer, x, B, ctx->idx_all, ctx->count_all, nullptr, y, nullptr,
+                         static_cast<hipStream_t>(stream));
+}
+
+pf_status pf_layer_step_auto(pf_ctx *ctx, const pf_layer *layer, const float *x, int B,
+                             float density_hint, float crossover, float *y, void *stream)
+{
+    if (!ctx) return PF_EINVAL;
+    if (!(crossover > 0.f && crossover <= 1.f) || !(density_hint >= 0.f))
+        return fail(ctx, PF_EINVAL, "crossover %g outside (0, 1] or negative density hint %g",
+                    (double)crossover, (double)density_hint);
+    if (density_hint >= crossover) return pf_dense_ffn(ctx, layer, x, B, y, stream);
+    return pf_layer_step(ctx, layer, x, B, y, stream);
+}
+
+pf_status pf_count_activations(pf_ctx *ctx, const pf_layer *layer, uint32_t *counts, void *stream)
+{
+    if (!ctx) return PF_EINVAL;
+    if (!layer || !counts) return fail(ctx, PF_EINVAL, "null argument");
+    if (layer->ctx != ctx) return fail(ctx, PF_EINVAL, "layer belongs to another context");
+    if (!ctx->last_idx) return fail(ctx, PF_EINVAL, "no layer step has run on this context");
+    hipLaunchKernelGGL(k_count_activations, dim3(64), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       ctx->last_idx, ctx->last_count, layer->desc.ffn, counts);
+    PF_HIP(ctx, hipGetLastError());
+    return PF_OK;
+}
+
 pf_status pf_ctx_last_active(pf_ctx *ctx, const uint64_t **mask_words, const int32_t **idx,
                              const int32_t **count)
 {
     if (!ctx) return PF_EINVAL;
-    if (mask_words) *mask_words = ctx->mask_words;
-    if (idx) *idx = ctx->idx;
-    if (count) *count = ctx->count;
+    if (mask_words) *mask_words = ctx->last_idx ? ctx->last_mask : ctx->mask_words;
+    if (idx) *idx = ctx->last_idx ? ctx->last_idx : ctx->idx;
+    if (count) *count = ctx->last_count ? ctx->last_count : ctx->count;
     return PF_OK;
 }
 

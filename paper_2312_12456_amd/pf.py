@@ -21,7 +21,8 @@ EXPORTS = [
     "pf_ctx_create", "pf_ctx_destroy", "pf_layer_create", "pf_layer_destroy", "pf_predict",
     "pf_compact", "pf_sparse_ffn", "pf_layer_step", "pf_ctx_last_active", "pf_stack_glue",
     "pf_stack_step", "pf_plan_create", "pf_plan_run", "pf_plan_destroy", "pf_strerror",
-    "pf_last_error", "pf_version", "pf_profile_begin", "pf_profile_end",
+    "pf_last_error", "pf_version", "pf_profile_begin", "pf_profile_end", "pf_dense_ffn",
+    "pf_layer_step_auto", "pf_count_activations",
 ]
 
 
@@ -71,6 +72,9 @@ def lib():
         L.pf_sparse_ffn.argtypes = [P, P, P, I, P, P, P, P]
         L.pf_layer_step.argtypes = [P, P, P, I, P, P]
         L.pf_ctx_last_active.argtypes = [P, PP, PP, PP]
+        L.pf_dense_ffn.argtypes = [P, P, P, I, P, P]
+        L.pf_layer_step_auto.argtypes = [P, P, P, I, ctypes.c_float, ctypes.c_float, P, P]
+        L.pf_count_activations.argtypes = [P, P, P, P]
         L.pf_stack_glue.argtypes = [P, P, P, I, I, P, P]
         L.pf_stack_step.argtypes = [P, PP, I, P, I, P, P]
         L.pf_plan_create.argtypes = [P, PP, I, P, I, P, P, PP]
@@ -157,6 +161,22 @@ class Context:
         B = x.shape[0]
         self.check(lib().pf_layer_step(self._h, layer._h, _dev_ptr(x, torch.float32, B * layer.d), B,
                                        _dev_ptr(y, torch.float32, B * layer.d), _stream_ptr(stream)))
+
+    def dense_ffn(self, layer, x, y, stream=None):
+        B = x.shape[0]
+        self.check(lib().pf_dense_ffn(self._h, layer._h, _dev_ptr(x, torch.float32, B * layer.d), B,
+                                      _dev_ptr(y, torch.float32, B * layer.d), _stream_ptr(stream)))
+
+    def layer_step_auto(self, layer, x, y, density_hint, crossover, stream=None):
+        B = x.shape[0]
+        self.check(lib().pf_layer_step_auto(self._h, layer._h, _dev_ptr(x, torch.float32, B * layer.d),
+                                            B, ctypes.c_float(density_hint), ctypes.c_float(crossover),
+                                            _dev_ptr(y, torch.float32, B * layer.d), _stream_ptr(stream)))
+
+    def count_activations(self, layer, counts, stream=None):
+        """counts [ffn] int32 on the device (non-negative values, read as uint32 by the library)."""
+        self.check(lib().pf_count_activations(self._h, layer._h, _dev_ptr(counts, torch.int32, layer.ffn),
+                                              _stream_ptr(stream)))
 
     def last_active(self):
         """(mask_words, idx, count) device addresses left by the last layer_step."""

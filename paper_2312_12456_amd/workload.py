@@ -202,6 +202,32 @@ def make_layer(cfg, layer, seed, device="cpu", pred_bias=True):
     return out
 
 
+NEURON_AXIS_KEYS = ("w_up", "w_gate", "w_down", "s_up", "s_gate", "s_down", "b_up", "p2", "p_bias")
+
+
+def permute_neurons(layer, order):
+    """The same layer with its neurons renumbered: new neuron j is old neuron order[j].
+
+    Every tensor with a neuron axis (rows of the three FFN matrices and their scales, FC1
+    bias, rows of the predictor's output layer and its bias, the target probabilities) is
+    reordered alike, so the FFN computes the same function and the predictor marks the same
+    neurons under their new numbers.  Used to lay neurons out hot-first from profiled counts
+    (the frequency-sorted layout a neuron table makes possible)."""
+    out = dict(layer)
+    for k in NEURON_AXIS_KEYS:
+        v = layer.get(k)
+        if v is None:
+            continue
+        if isinstance(v, torch.Tensor):
+            idx = torch.as_tensor(np.asarray(order), dtype=torch.long, device=v.device)
+            out[k] = v.index_select(0, idx).contiguous()
+        else:
+            out[k] = np.ascontiguousarray(np.asarray(v)[np.asarray(order)])
+    if layer.get("p") is not None:
+        out["p"] = np.asarray(layer["p"])[np.asarray(order)]
+    return out
+
+
 def make_inputs(cfg, token, seed, batch=1, device="cpu"):
     """Hidden states entering the stack at decode step `token`: [batch][d] ~ N(0, I)."""
     g = _generator("cpu", seed, "token", token, "batch", batch)

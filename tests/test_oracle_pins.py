@@ -386,3 +386,21 @@ def test_workload_is_seeded_and_layers_differ():
     assert all(np.array_equal(wl.to_host(a)[k], wl.to_host(b)[k]) for k in ("w_up", "p2", "b_up"))
     assert not np.array_equal(wl.to_host(a)["w_up"], wl.to_host(c)["w_up"])
     assert np.array_equal(wl.make_inputs(cfg, 3, 1).numpy(), wl.make_inputs(cfg, 3, 1).numpy())
+
+
+def test_neuron_permutation_leaves_the_function_unchanged(oracle):
+    """Renumbering the neurons (frequency-sorted layout) permutes the predictor's mask and
+    leaves dense, masked and predicted-mask outputs unchanged up to the order of an fp64 sum."""
+    for act, wtype in ((wl.ACT_RELU, wl.W_FP16), (wl.ACT_REGLU, wl.W_FP16), (wl.ACT_RELU, wl.W_INT4_G128)):
+        cfg = small_cfg(d=256, ffn=320, r=48, act=act, wtype=wtype, rate=0.2)
+        lay = wl.to_host(wl.make_layer(cfg, 0, seed=5))
+        order = np.random.Generator(np.random.PCG64(3)).permutation(cfg.ffn)
+        lay2 = wl.permute_neurons(lay, order)
+        O, O2 = oracle_layer(cfg, lay), oracle_layer(cfg, lay2)
+        x = wl.make_inputs(cfg, 0, seed=5, batch=2).numpy()
+        np.testing.assert_allclose(O2.dense_ffn(x), O.dense_ffn(x), rtol=0, atol=1e-12)
+        y, m = O.layer_step(x, return_mask=True)
+        y2, m2 = O2.layer_step(x, return_mask=True)
+        assert np.array_equal(m2, m[order]) and 0 < m.sum() < cfg.ffn
+        np.testing.assert_allclose(y2, y, rtol=0, atol=1e-12)
+        np.testing.assert_array_equal(O2.predict(x)["scores"], O.predict(x)["scores"][:, order])
