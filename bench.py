@@ -46,6 +46,9 @@ def parse_args():
     ap.add_argument("--sort-neurons", type=int, default=0, metavar="N",
                     help="profile activation counts over N tokens first and lay every layer's "
                          "neurons out hot-first (frequency-sorted layout)")
+    ap.add_argument("--lookahead", type=int, default=0, choices=[0, 1],
+                    help="1: look-ahead prediction at distance 1 (predictors overlap the sparse "
+                         "kernels of the layer before; lists differ from the default path)")
     ap.add_argument("--rate", type=float, default=None,
                     help="override the configuration's mean activation rate (scaling runs)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "pmc_traffic.json"),
@@ -169,6 +172,7 @@ def main():
             layers[l] = pf.Layer.from_workload(ctx, cfg, tensors[l])
         torch.cuda.synchronize()
 
+    ctx.set_lookahead(args.lookahead)
     plan = pf.Plan(ctx, layers, x_buf, out) if args.mode == "graph" else None
 
     def step(t):
@@ -307,6 +311,7 @@ def main():
                                   "int4-g128" if cfg.wtype == wl.W_INT4_G128 else "fp16",
                                   B, cfg.alpha, 100 * cfg.rate, K),
                    "launch": args.mode, "predictor_bias": not args.no_pred_bias,
+                   "lookahead": args.lookahead,
                    "neuron_layout": ("hot-first from %d profiled tokens" % args.sort_neurons)
                    if args.sort_neurons > 0 else "as generated"},
         "roofline": roofline,

@@ -156,6 +156,16 @@ pf_status pf_count_activations(pf_ctx *ctx, const pf_layer *layer, uint32_t *cou
 pf_status pf_ctx_last_active(pf_ctx *ctx, const uint64_t **mask_words, const int32_t **idx,
                              const int32_t **count);
 
+/* Look-ahead prediction (Sec. 2.1: the activations of a layer can be predicted a few layers
+ * ahead, from an earlier layer's input).  With distance 1, pf_stack_step and the plans
+ * created afterwards take the active set of layer l >= 1 from layer l's predictor applied to
+ * the INPUT of layer l-1 (layer 0: its own input), and run the predictors on a second stream
+ * of the library beside the sparse kernels of the layer before, so that a layer costs
+ * max(predictor, sparse FFN) instead of their sum.  This changes which neurons are listed
+ * (an approximation whose accuracy depends on trained predictors and is not measured here);
+ * every other call is unaffected.  distance: 0 (off, the default) or 1. */
+pf_status pf_ctx_set_lookahead(pf_ctx *ctx, int distance);
+
 /* Glue of the synthetic FFN stack used for benchmarking (not in the paper): residual add
  * and scale-only RMS normalisation, x_next = (x + y) * sqrt(d) / ||x + y||_2 per token. */
 pf_status pf_stack_glue(pf_ctx *ctx, const float *x, const float *y, int d, int B,

@@ -239,5 +239,25 @@ def stack_glue(x, y):
     return out
 
 
+def stack_lookahead(layers, x0):
+    """A stack of layers with look-ahead prediction at distance 1 (PowerInfer Sec. 2.1: the
+    activations of a layer can be predicted from an earlier layer's input): the active set of
+    layer l >= 1 is layer l's predictor applied to the input of layer l - 1; layer 0 uses its
+    own input.  Between layers the stack glue.  -> (output of the stack [B][d] fp32,
+    list of the masks used)."""
+    x = np.ascontiguousarray(np.asarray(x0), dtype=np.float32)
+    if x.ndim == 1:
+        x = x[None, :]
+    inputs, masks = [], []
+    for l, layer in enumerate(layers):
+        inputs.append(x)
+        seen = inputs[0] if l == 0 else inputs[l - 1]
+        mask = layer.predict(seen)["active"]
+        masks.append(mask)
+        y = layer.masked_ffn(x, mask)
+        x = stack_glue(x, y)
+    return x, masks
+
+
 def half_to_double(bits):
     return float(lib().pfo_half_to_double(int(bits)))

@@ -57,6 +57,11 @@ struct pf_ctx {
     float *ypart = nullptr;          // [4][max_batch][max_d] FC2 output as partial sums
     float *xbuf[2] = {nullptr, nullptr};  // [max_batch][max_d] layer inputs inside pf_stack_step
     hipStream_t capture_stream = nullptr;
+    // look-ahead mode: predictors on a stream of their own, masks double-buffered
+    int lookahead = 0;
+    hipStream_t side_stream = nullptr;
+    uint64_t *mask_words2 = nullptr;        // [max_ffn / 64]
+    std::vector<hipEvent_t> la_events;      // fork / join events, created on demand
     // per-kernel timing with HIP events (pf_profile_begin / pf_profile_end)
     bool prof_on = false;
     bool capturing = false;
@@ -477,9 +482,72 @@ pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int ny, int d
 
 // One decode step of the stack.  The glue between layer l-1 and layer l runs inside layer
 // l's hidden-layer kernel; only the glue after the last layer is a kernel of its own.
+// Event number `i` of the look-ahead schedule (created on demand, reused by later calls).
+hipEvent_t la_event(pf_ctx *ctx, size_t i)
+{
+    while (ctx->la_events.size() <= i) {
+        hipEvent_t e = nullptr;
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
+        ctx->la_events.push_back(e);
+    }
+    return ctx->la_events[i];
+}
+
+// One decode step with look-ahead prediction at distance 1: the predictor of layer l reads
+// the input of layer l-1 (layer 0 and 1: the stack's input) and runs on the side stream
+// while the main stream is busy with the sparse kernels of layer l-1.  Masks alternate
+// between two buffers; the glue is a kernel of its own on the main stream.
+pf_status stack_enqueue_lookahead(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x,
+                                  int B, float *x_out, hipStream_t st)
+{
+    hipStream_t side = ctx->side_stream;
+    uint64_t *masks[2] = {ctx->mask_words, ctx->mask_words2};
+    const int d = layers[0]->desc.d;
+    // events: 0 = fork, 1 + l = mask of layer l ready, 1 + n_layers + l = input of layer l ready
+    hipEvent_t fork = la_event(ctx, 0);
+    if (!la_event(ctx, 2 * (size_t)n_layers + 1) || !fork) return fail(ctx, PF_EHIP, "hipEventCreate failed");
+    auto ev_mask = [&](int l) { return ctx->la_events[1 + (size_t)l]; };
+    auto ev_input = [&](int l) { return ctx->la_events[1 + (size_t)n_layers + (size_t)l]; };
+    PF_HIP(ctx, hipEventRecord(fork, st));
+    PF_HIP(ctx, hipStreamWaitEvent(side, fork, 0));
+    auto predict_on_side = [&](int l, const float *seen) -> pf_status {
+        pf_status s = launch_predict(ctx, layers[l], seen, nullptr, 0, nullptr, B, nullptr, masks[l & 1], side);
+        if (s != PF_OK) return s;
+        PF_HIP(ctx, hipEventRecord(ev_mask(l), side));
+        return PF_OK;
+    };
+    pf_status s = predict_on_side(0, x);
+    if (s == PF_OK && n_layers > 1) s = predict_on_side(1, x);
+    if (s != PF_OK) return s;
+    int ny = 1;
+    const float *cur = x;
+    for (int l = 0; l < n_layers; ++l) {
+        PF_HIP(ctx, hipStreamWaitEvent(st, ev_mask(l), 0));
+        ctx->last_mask = masks[l & 1];
+        ctx->last_idx = ctx->idx;
+        ctx->last_count = ctx->count;
+        s = launch_sparse(ctx, layers[l], cur, B, nullptr, nullptr, masks[l & 1], nullptr, &ny, st);
+        if (s != PF_OK) return s;
+        if (l + 1 < n_layers) {
+            float *xn = ctx->xbuf[(l + 1) & 1];
+            s = launch_glue(ctx, cur, ctx->ypart, ny, d, B, xn, st);
+            if (s != PF_OK) return s;
+            cur = xn;
+            if (l + 2 < n_layers) {  // layer l+2 is predicted from the input of layer l+1
+                PF_HIP(ctx, hipEventRecord(ev_input(l + 1), st));
+                PF_HIP(ctx, hipStreamWaitEvent(side, ev_input(l + 1), 0));
+                s = predict_on_side(l + 2, xn);
+                if (s != PF_OK) return s;
+            }
+        }
+    }
+    return launch_glue(ctx, cur, ctx->ypart, ny, d, B, x_out, st);
+}
+
 pf_status stack_enqueue(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x, int B,
                         float *x_out, hipStream_t st)
 {
+    if (ctx->lookahead) return stack_enqueue_lookahead(ctx, layers, n_layers, x, B, x_out, st);
     int ny = 1;            // partial sums FC2 left in ctx->ypart
     const float *cur = x;  // input of the layer being enqueued (raw input of the previous one
                            // until the hidden kernel has formed it)
@@ -605,6 +673,7 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         PF_ALLOC(ctx->idx, (size_t)max_ffn * sizeof(int32_t));
         PF_ALLOC(ctx->count, 64);
         PF_ALLOC(ctx->idx_all, (size_t)max_ffn * sizeof(int32_t));
+        PF_ALLOC(ctx->mask_words2, (size_t)(max_ffn / 64) * sizeof(uint64_t));
         PF_ALLOC(ctx->count_all, 64);
         PF_ALLOC(ctx->h, (size_t)pf::h_stride(max_batch) * max_ffn * sizeof(float));
         PF_ALLOC(ctx->ypart, (size_t)pf::kDown2MaxSplit * max_batch * max_d * sizeof(float));
@@ -619,6 +688,7 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         }
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->capture_stream, hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->side_stream, hipStreamNonBlocking);
         if (e != hipSuccess) { st = PF_EHIP; break; }
     } while (0);
     if (st != PF_OK) {
@@ -640,6 +710,9 @@ void pf_ctx_destroy(pf_ctx *ctx)
     (void)hipFree(ctx->idx);
     (void)hipFree(ctx->count);
     (void)hipFree(ctx->idx_all);
+    (void)hipFree(ctx->mask_words2);
+    if (ctx->side_stream) (void)hipStreamDestroy(ctx->side_stream);
+    for (hipEvent_t e : ctx->la_events) (void)hipEventDestroy(e);
     (void)hipFree(ctx->count_all);
     (void)hipFree(ctx->h);
     (void)hipFree(ctx->ypart);
@@ -795,6 +868,14 @@ pf_status pf_stack_glue(pf_ctx *ctx, const float *x, const float *y, int d, int 
     if (!x || !y || !x_next) return fail(ctx, PF_EINVAL, "null argument");
     if (d < 1 || B < 1) return fail(ctx, PF_EINVAL, "non-positive size");
     return launch_glue(ctx, x, y, 1, d, B, x_next, static_cast<hipStream_t>(stream));
+}
+
+pf_status pf_ctx_set_lookahead(pf_ctx *ctx, int distance)
+{
+    if (!ctx) return PF_EINVAL;
+    if (distance != 0 && distance != 1) return fail(ctx, PF_EINVAL, "look-ahead distance %d: 0 or 1", distance);
+    ctx->lookahead = distance;
+    return PF_OK;
 }
 
 pf_status pf_stack_step(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x, int B,

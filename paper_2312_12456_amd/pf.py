@@ -22,7 +22,7 @@ EXPORTS = [
     "pf_compact", "pf_sparse_ffn", "pf_layer_step", "pf_ctx_last_active", "pf_stack_glue",
     "pf_stack_step", "pf_plan_create", "pf_plan_run", "pf_plan_destroy", "pf_strerror",
     "pf_last_error", "pf_version", "pf_profile_begin", "pf_profile_end", "pf_dense_ffn",
-    "pf_layer_step_auto", "pf_count_activations",
+    "pf_layer_step_auto", "pf_count_activations", "pf_ctx_set_lookahead",
 ]
 
 
@@ -75,6 +75,7 @@ def lib():
         L.pf_dense_ffn.argtypes = [P, P, P, I, P, P]
         L.pf_layer_step_auto.argtypes = [P, P, P, I, ctypes.c_float, ctypes.c_float, P, P]
         L.pf_count_activations.argtypes = [P, P, P, P]
+        L.pf_ctx_set_lookahead.argtypes = [P, I]
         L.pf_stack_glue.argtypes = [P, P, P, I, I, P, P]
         L.pf_stack_step.argtypes = [P, PP, I, P, I, P, P]
         L.pf_plan_create.argtypes = [P, PP, I, P, I, P, P, PP]
@@ -177,6 +178,9 @@ class Context:
         """counts [ffn] int32 on the device (non-negative values, read as uint32 by the library)."""
         self.check(lib().pf_count_activations(self._h, layer._h, _dev_ptr(counts, torch.int32, layer.ffn),
                                               _stream_ptr(stream)))
+
+    def set_lookahead(self, distance):
+        self.check(lib().pf_ctx_set_lookahead(self._h, int(distance)))
 
     def last_active(self):
         """(mask_words, idx, count) device addresses left by the last layer_step."""

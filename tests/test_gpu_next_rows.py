@@ -104,3 +104,62 @@ def test_count_activations_equals_oracle_counts(pf):
     ctx.count_activations(L, counts)
     torch.cuda.synchronize()
     assert np.array_equal(counts.cpu().numpy(), got + 1)
+
+
+@pytest.mark.parametrize("B", [1, 4])
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
+def test_stack_lookahead_matches_oracle(pf, act, B):
+    """Look-ahead prediction at distance 1 through pf_stack_step and a recorded plan (two
+    streams inside the library) against the oracle's look-ahead stack: final output within the
+    output bar, last layer's list bit exact.  A seed is used only if no oracle score of any
+    layer lies within 1e-4 of the threshold, so that no decision can differ by rounding."""
+    from oracle import pf_oracle
+    n_layers = 4
+    cfg = small_cfg(d=520, ffn=1344, r=136, act=act, rate=0.1, layers=n_layers)
+    for seed in range(40, 60):
+        lays = [wl.make_layer(cfg, l, seed, device="cuda") for l in range(n_layers)]
+        Os = [oracle_layer(cfg, wl.to_host(t)) for t in lays]
+        x = wl.make_inputs(cfg, 0, seed=seed, batch=B, device="cuda")
+        ref, masks = pf_oracle.stack_lookahead(Os, x.cpu().numpy())
+        # replay the oracle's inputs to look at its scores
+        xs, xi = [], x.cpu().numpy()
+        for l in range(n_layers):
+            xs.append(xi)
+            xi = pf_oracle.stack_glue(xi, Os[l].masked_ffn(xi, masks[l]))
+        margin = min(np.abs(Os[l].predict(xs[max(l - 1, 0)])["scores"] - cfg.threshold).min()
+                     for l in range(n_layers))
+        if margin >= 1e-4:
+            break
+    else:
+        pytest.skip("no seed with a clear margin")
+    ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
+    Ls = [pf.Layer.from_workload(ctx, cfg, t) for t in lays]
+    # the plain stack differs (other lists from layer 1 on) ...
+    plain = torch.empty_like(x)
+    ctx.stack_step(Ls, x, plain)
+    torch.cuda.synchronize()
+    ctx.set_lookahead(1)
+    out = torch.full_like(x, float("nan"))
+    ctx.stack_step(Ls, x, out)
+    torch.cuda.synchronize()
+    check_output(out.cpu().numpy(), ref, "look-ahead stack")
+    assert not torch.allclose(out, plain, atol=1e-3)
+    _, lst = _last_list(pf, ctx, cfg.ffn)
+    assert np.array_equal(lst, np.flatnonzero(masks[-1]))
+    # ... and the recorded plan replays it
+    out2 = torch.zeros_like(x)
+    plan = pf.Plan(ctx, Ls, x, out2)
+    for _ in range(3):
+        out2.zero_()
+        plan.run()
+        torch.cuda.synchronize()
+        assert torch.equal(out2, out)
+        _ = (x + 1).sum().item()
+    plan.close()
+    ctx.set_lookahead(0)
+    again = torch.empty_like(x)
+    ctx.stack_step(Ls, x, again)
+    torch.cuda.synchronize()
+    assert torch.equal(again, plain)
+    with pytest.raises(pf.PfError):
+        ctx.set_lookahead(2)

@@ -404,3 +404,39 @@ def test_neuron_permutation_leaves_the_function_unchanged(oracle):
         assert np.array_equal(m2, m[order]) and 0 < m.sum() < cfg.ffn
         np.testing.assert_allclose(y2, y, rtol=0, atol=1e-12)
         np.testing.assert_array_equal(O2.predict(x)["scores"], O.predict(x)["scores"][:, order])
+
+
+def test_stack_lookahead_reads_the_previous_layers_input(oracle):
+    """Look-ahead at distance 1, pinned with selector predictors whose active set can be read
+    off the vector they are given: neuron m fires iff coordinate m of that vector is positive.
+    Layer l >= 1 must list the sign pattern of the INPUT of layer l-1 -- not of its own input,
+    which the layers here flip on purpose -- and layer 0 that of its own input."""
+    d, F, r = 16, 16, 16
+    eye = np.eye(d, dtype=np.float16)
+
+    def layer(flip):
+        # FFN: h_m = ReLU(x_m) on the listed coordinates, y = -2 h when flip (so that a listed
+        # positive coordinate changes sign in x + y), else y = 0
+        w_up = eye.copy()
+        w_down = (-2.0 * eye if flip else 0.0 * eye).astype(np.float16)
+        return oracle.Layer(d, F, r, w_up=w_up, w_down=w_down, p1=eye, p2=eye)
+
+    layers = [layer(True), layer(False), layer(False)]
+    x0 = np.array([[3, -1, 2, -4, 1, 5, -2, 6, -3, 1, 2, -1, 4, -5, 1, 2]], np.float32)
+    out, masks = oracle.stack_lookahead(layers, x0)
+    pos0 = x0[0] > 0
+    assert np.array_equal(masks[0], pos0)            # layer 0: own input
+    assert np.array_equal(masks[1], pos0)            # layer 1: input of layer 0
+    # input of layer 1 = glue(x0 + y0): positive listed coordinates flipped, the rest kept
+    x1 = x0[0].astype(np.float64).copy()
+    x1[pos0] *= -1.0
+    x1 *= np.sqrt(d) / np.linalg.norm(x1)
+    assert not np.array_equal(x1 > 0, pos0)
+    assert np.array_equal(masks[2], x1 > 0)          # layer 2: input of layer 1
+    # layers 1 and 2 add nothing, so the output is the input of layer 1 (already unit rms)
+    np.testing.assert_allclose(out[0], x1, rtol=0, atol=1e-6)
+    # one layer: look-ahead is the plain layer step followed by the glue
+    y, m = layers[0].layer_step(x0, return_mask=True)
+    o1, m1 = oracle.stack_lookahead(layers[:1], x0)
+    assert np.array_equal(m1[0], m)
+    np.testing.assert_array_equal(o1, oracle.stack_glue(x0, y))
