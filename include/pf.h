@@ -167,7 +167,9 @@ pf_status pf_ctx_last_active(pf_ctx *ctx, const uint64_t **mask_words, const int
 pf_status pf_ctx_set_lookahead(pf_ctx *ctx, int distance);
 
 /* Glue of the synthetic FFN stack used for benchmarking (not in the paper): residual add
- * and scale-only RMS normalisation, x_next = (x + y) * sqrt(d) / ||x + y||_2 per token. */
+ * and scale-only RMS normalisation, x_next = s * (x + y) * sqrt(d) / ||x + y||_2 per token,
+ * where s is a fixed +/-1 pattern over (batch row, column) that is all +1 for row 0: it keeps
+ * the rows of a batch from aligning over the layers of a stack. */
 pf_status pf_stack_glue(pf_ctx *ctx, const float *x, const float *y, int d, int B,
                         float *x_next, void *stream);
 

@@ -381,9 +381,29 @@ void pfo_layer_step(const pfo_layer *L, const float *x, int B, double *y, uint8_
 }
 
 /*
+ * Sign that the glue gives column c of batch row b: +1 for row 0, otherwise the top bit of
+ * a fixed integer mix of (b, c) -- a counter-based pattern, the same for every call.
+ */
+static double pfo_glue_sign(uint32_t b, uint32_t c)
+{
+    if (b == 0) return 1.0;
+    uint32_t h = b * 0x9E3779B1u + c * 0x85EBCA77u + 0x165667B1u;
+    h ^= h >> 15;
+    h *= 0x2C1B3C6Du;
+    h ^= h >> 12;
+    h *= 0x297A2D39u;
+    h ^= h >> 15;
+    return (h >> 31) ? -1.0 : 1.0;
+}
+
+/*
  * Glue between the layers of the synthetic FFN stack (a benchmark construction, not in
  * the paper): residual add followed by a scale-only RMS normalisation,
- *   v = x + y,  x_next = v * sqrt(d) / ||v||_2     (per token; v == 0 stays 0).
+ *   v = x + y,  x_next = sign(b, c) * v * sqrt(d) / ||v||_2     (per token; v == 0 stays 0).
+ * The fixed sign pattern of the rows b >= 1 keeps the tokens of a batch from aligning: the
+ * always-active neurons add nearly the same vector to every row, and without it the rows of
+ * a batch would list the same neurons after a few layers (the union over the batch, whose
+ * growth is what a batched step is about, would collapse to one token's set).
  * The result is rounded to fp32 because activations travel between layers in fp32.
  */
 void pfo_stack_glue(const float *x, const double *y, int d, int B, float *x_next)
@@ -397,7 +417,7 @@ void pfo_stack_glue(const float *x, const double *y, int d, int B, float *x_next
         double scale = ss > 0.0 ? sqrt((double)d / ss) : 0.0;
         for (int c = 0; c < d; ++c) {
             double v = (double)x[(size_t)b * d + c] + y[(size_t)b * d + c];
-            x_next[(size_t)b * d + c] = (float)(v * scale);
+            x_next[(size_t)b * d + c] = (float)(pfo_glue_sign((uint32_t)b, (uint32_t)c) * v * scale);
         }
     }
 }

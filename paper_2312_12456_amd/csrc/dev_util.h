@@ -97,6 +97,29 @@ __device__ __forceinline__ void butterfly_halve(float (&a)[N], int lane)
     }
 }
 
+// Sign bit (0 or 0x80000000) the stack glue gives column c of batch row b: none for row 0,
+// otherwise the top bit of a fixed integer mix of (b, c).  It decorrelates the rows of a
+// batch, which the always-active neurons would otherwise align within a few layers.
+__device__ __forceinline__ uint32_t glue_sign_bit(uint32_t b, uint32_t c)
+{
+    if (b == 0) return 0u;
+    uint32_t h = b * 0x9E3779B1u + c * 0x85EBCA77u + 0x165667B1u;
+    h ^= h >> 15;
+    h *= 0x2C1B3C6Du;
+    h ^= h >> 12;
+    h *= 0x297A2D39u;
+    h ^= h >> 15;
+    return h & 0x80000000u;
+}
+
+__device__ __forceinline__ float4 glue_signed(float4 v, uint32_t b, uint32_t c0)
+{
+    return make_float4(__uint_as_float(__float_as_uint(v.x) ^ glue_sign_bit(b, c0)),
+                       __uint_as_float(__float_as_uint(v.y) ^ glue_sign_bit(b, c0 + 1)),
+                       __uint_as_float(__float_as_uint(v.z) ^ glue_sign_bit(b, c0 + 2)),
+                       __uint_as_float(__float_as_uint(v.w) ^ glue_sign_bit(b, c0 + 3)));
+}
+
 // Buffer resources: every weight and activation load goes through a raw buffer descriptor
 // (base, byte size) held in scalar registers.  Lanes whose offset lies past the end get
 // zeros from the hardware, so loads need no branches -- which also lets the compiler count

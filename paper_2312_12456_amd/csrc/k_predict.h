@@ -23,14 +23,16 @@ constexpr int kPredWaves = kPredThreads / kWave;
 // scale-only RMS norm): every block stages v = xp + yp, reduces ||v||^2 itself and applies
 // the scale to its dot products; block 0 also writes x for the kernels that follow.
 // yp may arrive as ny <= 4 partial sums, ypstride floats apart (row-split FC2): they are
-// added in the fixed order 0 .. ny-1.
+// added in the fixed order 0 .. ny-1.  b0 = batch row of the first token this launch handles
+// (the glue's sign pattern depends on the row).
 template <int B, bool GLUE>
 __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__restrict__ p1,
                                                               const float *__restrict__ x,
                                                               const float *__restrict__ yp, int ny,
                                                               int ypstride,
                                                               float *__restrict__ x_new,
-                                                              float *__restrict__ t, int d, int r)
+                                                              float *__restrict__ t, int d, int r,
+                                                              int b0)
 {
     extern __shared__ float xs[];
     __shared__ float ss_w[kPredWaves][B];
@@ -87,7 +89,8 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
                         const float4 q = vp[s][b][p - 1];
                         c = make_float4(c.x + q.x, c.y + q.y, c.z + q.z, c.w + q.w);
                     }
-                    const float4 v = make_float4(a.x + c.x, a.y + c.y, a.z + c.z, a.w + c.w);
+                    const float4 v = glue_signed(make_float4(a.x + c.x, a.y + c.y, a.z + c.z, a.w + c.w),
+                                                 (uint32_t)b0 + (uint32_t)b, (uint32_t)e);
                     ss[b] = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss[b]))));
                     *reinterpret_cast<float4 *>(xs + (e < kpad ? b * kpad + lds_slot(e) : B * kpad)) = v;
                 }

@@ -272,7 +272,7 @@ __global__ __launch_bounds__(256) void k_combine(const float *__restrict__ part,
 }
 
 // ---------------------------------------------------------------------------------------
-// Stack glue: x_next[b] = (x[b] + y[b]) * sqrt(d) / ||x[b] + y[b]||_2.  grid = B.
+// Stack glue: x_next[b] = sign(b, .) * (x[b] + y[b]) * sqrt(d) / ||x[b] + y[b]||_2.  grid = B.
 constexpr int kGlueThreads = 1024;
 
 // x_next may alias x: every element is read and written by the same thread.
@@ -307,7 +307,8 @@ __global__ __launch_bounds__(kGlueThreads) void k_glue(const float *x, const flo
 #pragma unroll
         for (int q = 1; q < kGlueMaxParts; ++q)
             t = make_float4(t.x + p[i][q].x, t.y + p[i][q].y, t.z + p[i][q].z, t.w + p[i][q].w);
-        v[i] = make_float4(v[i].x + t.x, v[i].y + t.y, v[i].z + t.z, v[i].w + t.w);
+        v[i] = glue_signed(make_float4(v[i].x + t.x, v[i].y + t.y, v[i].z + t.z, v[i].w + t.w), (uint32_t)b,
+                           (uint32_t)((i * kGlueThreads + (int)threadIdx.x) * 4));
         ss = fmaf(v[i].x, v[i].x, fmaf(v[i].y, v[i].y, fmaf(v[i].z, v[i].z, fmaf(v[i].w, v[i].w, ss))));
     }
     ss = wave_sum(ss);
@@ -351,7 +352,10 @@ __global__ __launch_bounds__(kGlueThreads) void k_glue_long(const float *x, cons
 #pragma unroll
     for (int k = 0; k < kGlueThreads / kWave; ++k) tot += wsum[k];
     const float scale = tot > 0.f ? sqrtf((float)d / tot) : 0.f;
-    for (int c = threadIdx.x; c < d; c += kGlueThreads) x_next[(size_t)b * d + c] = (xb[c] + ysum(c)) * scale;
+    for (int c = threadIdx.x; c < d; c += kGlueThreads) {
+        const float v = (xb[c] + ysum(c)) * scale;
+        x_next[(size_t)b * d + c] = __uint_as_float(__float_as_uint(v) ^ glue_sign_bit((uint32_t)b, (uint32_t)c));
+    }
 }
 
 }  // namespace pf

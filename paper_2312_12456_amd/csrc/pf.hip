@@ -266,12 +266,12 @@ pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const fl
             PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_pred_hidden<BT, true>), grid,
                                                dim3(pf::kPredThreads), lds, st, p1, x + xo,
                                                glue_y + xo, glue_ny, B * D.d, x_new + xo,
-                                               ctx->t + (size_t)b0 * D.r, D.d, D.r));
+                                               ctx->t + (size_t)b0 * D.r, D.d, D.r, b0));
         } else {
             PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_pred_hidden<BT, false>), grid,
                                                dim3(pf::kPredThreads), lds, st, p1, x + xo,
                                                (const float *)nullptr, 0, 0, (float *)nullptr,
-                                               ctx->t + (size_t)b0 * D.r, D.d, D.r));
+                                               ctx->t + (size_t)b0 * D.r, D.d, D.r, b0));
         }
     }
     PF_HIP(ctx, hipGetLastError());

@@ -341,11 +341,34 @@ def test_stack_glue_norm_and_direction(oracle):
     y = rng.standard_normal((3, 40))
     out = oracle.stack_glue(x, y)
     v = x.astype(np.float64) + y
+    want = v * np.sqrt(40.0) / np.linalg.norm(v, axis=1)[:, None]
     np.testing.assert_allclose(np.sum(out.astype(np.float64) ** 2, axis=1), 40.0, rtol=1e-6)
-    np.testing.assert_allclose(out, v * np.sqrt(40.0) / np.linalg.norm(v, axis=1)[:, None],
-                               rtol=1e-6)
+    np.testing.assert_allclose(out[0], want[0], rtol=1e-6)            # row 0: no sign change
+    np.testing.assert_allclose(np.abs(out), np.abs(want), rtol=1e-6)  # other rows: magnitudes kept
     assert np.array_equal(oracle.stack_glue(np.zeros((1, 8), np.float32), np.zeros((1, 8))),
                           np.zeros((1, 8), np.float32))
+
+
+def test_stack_glue_sign_pattern_decorrelates_rows(oracle):
+    """Rows b >= 1 get a fixed +/-1 pattern: the same whatever the values, balanced, different
+    from row to row, and it turns identical rows into nearly orthogonal ones."""
+    d, B = 4096, 8
+    ones = np.ones((B, d), np.float32)
+    s = oracle.stack_glue(ones, np.zeros((B, d)))       # = the pattern itself (unit rms input)
+    assert np.array_equal(np.abs(s), ones) and np.array_equal(s[0], ones[0])
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((B, d)).astype(np.float32)
+    y = rng.standard_normal((B, d))
+    out = oracle.stack_glue(x, y)
+    assert np.array_equal(np.sign(out), np.sign(x + y) * s)  # independent of the values
+    for b in range(1, B):
+        assert abs(s[b].mean()) < 0.06                       # balanced: |mean| < 4 sigma
+        for b2 in range(b):
+            assert abs(np.mean(s[b] * s[b2])) < 0.07         # rows uncorrelated
+    same = np.tile(x[:1], (B, 1))
+    o = oracle.stack_glue(same, np.zeros((B, d))).astype(np.float64)
+    cos = (o @ o.T) / d
+    assert np.all(np.abs(cos[np.triu_indices(B, 1)]) < 0.08)
 
 
 # ------------------------------------------------- I7: the generator's statistics
