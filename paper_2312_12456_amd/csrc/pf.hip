@@ -41,6 +41,10 @@ struct pf_ctx {
     int up_grid_cap = 2048;
     int up_grid_cap_i4 = 512;
     int mfma_grid = 256;
+    // The hidden layer goes to the matrix cores only above this B * d: below it the vector kernel
+    // with the glue fused in beats MFMA + a glue kernel of its own (measured: +1..3 % on the
+    // stack at 4 x 4096 and 4 x 5120, -9 % and worse from 8 x 4096 on).
+    int hidden_mfma_min_elems = 20480;
     int lds_budget = kLdsDefault;  // dynamic LDS a kernel of this context may request
     int down_split = 0;            // PF_DOWN_SPLIT: row groups of FC2 (0 = from the CU count)
     int mfma_min_batch = 4;        // FC1 goes to the matrix cores from this batch size on
@@ -240,7 +244,7 @@ pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const fl
     const pf_layer_desc &D = L->desc;
     if (!L->w.p1 || !L->w.p2) return fail(ctx, PF_EINVAL, "layer has no predictor weights");
     const __half *p1 = static_cast<const __half *>(L->w.p1);
-    if (pred_mfma(ctx, D.d, B)) {
+    if (pred_mfma(ctx, D.d, B) && (size_t)B * (size_t)D.d > (size_t)ctx->hidden_mfma_min_elems) {
         // a batch on the matrix cores; the glue, if any, as a kernel of its own in front
         if (glue_y) {
             pf_status s = launch_glue(ctx, x, glue_y, glue_ny, D.d, B, x_new, st);
@@ -636,6 +640,7 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         ctx->up_grid_cap = 8 * ctx->num_cu;
         ctx->up_grid_cap_i4 = 2 * ctx->num_cu;
         ctx->mfma_grid = ctx->num_cu;
+        if (const char *v = getenv("PF_HIDDEN_MFMA_MIN_ELEMS")) ctx->hidden_mfma_min_elems = atoi(v);
         if (const char *v = getenv("PF_MFMA_GRID")) {
             int c = atoi(v);
             if (c >= 1 && c <= 65535) ctx->mfma_grid = c;
