@@ -25,12 +25,10 @@ typedef float float4v_t __attribute__((ext_vector_type(4)));
 
 constexpr int kMfmaThreads = 512;
 constexpr int kMfmaWaves = kMfmaThreads / kWave;  // the waves of a block split K between them
-constexpr int kMfmaRows = 32;                     // list slots per block pass: two MFMA tiles
-constexpr int kMfmaKC = 128;                      // elements of d per chunk (4 MFMA K steps)
-constexpr int kMfmaSteps = kMfmaKC / 32;
-// LDS image of one chunk of one matrix: 32 rows x 256 bytes, written by 8 instructions of
-// 4 rows each (a quarter-wave per row, 16 pieces of 16 bytes)
-constexpr int kMfmaSlotBytes = kMfmaRows * kMfmaKC * 2;
+// LDS image of one chunk of one matrix in a wave's slot: R rows x KC halfs = 8 KB, for
+// R = 32 rows (two MFMA tiles) x 128 elements or R = 16 rows x 256 elements.  The fewer rows a
+// block has, the longer its chunks: the bytes in flight per wave stay the same.
+constexpr int kMfmaSlotBytes = 8192;
 
 // dynamic LDS of k_up_mfma: [mask words | prefix] when compacting itself, then one slot per
 // wave and matrix
@@ -62,32 +60,190 @@ __device__ __forceinline__ void split_hi_lo(const float4 &a, const float4 &b, ha
     }
 }
 
-// Put chunk `c` of the 32 rows of a pass in flight towards `slot`.  Instruction i moves rows
-// 4i .. 4i+3, one per quarter-wave, 16 pieces of 16 bytes each: a row's 256 bytes are two
-// whole lines.  Row R stores piece p at position p ^ swz(R), swz(R) = 2 * (R & 3) + ((R >> 2) & 1),
-// so that the 8 rows a group of 8 lanes reads together (same piece) fall into 8 different
-// 16-byte bank groups.  rowoff[i] = byte offset of this lane's row of instruction i in the
-// matrix (kOobOffset: no row).
-__device__ __forceinline__ int mfma_swz(int row) { return 2 * (row & 3) + ((row >> 2) & 1); }
-
+// Put chunk `c` (KC = 4096 / R elements) of the R rows of a pass in flight towards `slot`.  One
+// instruction moves 1 KB: 2 KC bytes (whole lines) of each of 512 / KC rows.  Row r stores
+// 16-byte piece p at position p ^ (r & 7), so that the 8 rows a group of 8 lanes reads together
+// (same piece) fall into 8 different 16-byte bank groups.  rowoff[i] = byte offset of this
+// lane's row of instruction i in the matrix (kOobOffset: no row).
+template <int R>
 __device__ __forceinline__ void mfma_issue_chunk(rsrc_t w, char *slot, const uint32_t (&rowoff)[8],
                                                  int c, int d, int lane)
 {
-    const int q = lane >> 4, p = lane & 15;
+    constexpr int KC = kMfmaSlotBytes / 2 / R;
+    constexpr int RPI = 512 / KC, LPR = 64 / RPI;  // rows per instruction, lanes per row
+    const int rin = lane / LPR, p = lane % LPR;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const int piece = p ^ (2 * q + (i & 1));  // = p ^ swz(4i + q)
-        const int k = c * kMfmaKC + piece * 8;
+        const int piece = p ^ ((RPI * i + rin) & 7);
+        const int k = c * KC + piece * 8;
         const uint32_t off = (k < d && rowoff[i] != kOobOffset) ? rowoff[i] + (uint32_t)k * 2u : kOobOffset;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(w, (lds_ptr_t)(slot + i * 1024), 16, (int)off, 0, 0, 0);
     }
 }
 
-// grid = G blocks; block b owns the list slots [b * rpb, (b + 1) * rpb), rpb = ceil(n / G),
-// in passes of 32 (an even share of the rows for every CU: with whole tiles dealt round-robin
-// the CUs that get one tile more than the others set the kernel's time).  The 8 waves of a
-// block take the chunks of d round-robin (wave w: chunks w, w + 8, ...) for the same rows and
-// their C tiles are added in LDS in wave order.  d % 32 == 0, B <= 16.
+// What the passes of a block need from the kernel around them.
+struct UpMfmaArgs {
+    rsrc_t wu, wg, xr;
+    const float *b_up;
+    const int32_t *idx_in;
+    int32_t *idx_out;
+    float *h;
+    const uint64_t *words_lds;
+    const uint32_t *pre_lds;
+    char *slots;
+    int *irow;
+    int B, hs, d, ffn, n, nwords, top_step, j_begin, j_end;
+};
+
+// The list slots [j_begin, j_end) of a block in passes of R rows (R / 16 MFMA tiles).
+template <int R, int ACT, bool FROM_MASK>
+__device__ __forceinline__ void up_mfma_passes(const UpMfmaArgs &a)
+{
+    constexpr bool GATED = (ACT == 1);
+    constexpr int NM = GATED ? 2 : 1;
+    constexpr int T = R / 16;                      // tiles per pass
+    constexpr int KC = kMfmaSlotBytes / 2 / R;     // elements of d per chunk
+    constexpr int STEPS = KC / 32;                 // MFMA K steps per chunk
+    constexpr int RPI = 512 / KC, LPR = 64 / RPI;
+    const int lane = threadIdx.x & 63, wave = wave_uniform(threadIdx.x >> 6);
+    const int row16 = lane & 15, kg = lane >> 4;
+    char *slot = a.slots + (size_t)wave * NM * kMfmaSlotBytes;  // this wave's: up, then gate
+    const int d = a.d, n = a.n;
+    const uint32_t xoff = row16 < a.B ? ((uint32_t)row16 * (uint32_t)d + (uint32_t)kg * 8u) * 4u : kOobOffset;
+    const int nchunks = (d + KC - 1) / KC;
+
+    for (int j0 = a.j_begin; j0 < a.j_end; j0 += R) {
+        // list slot -> neuron id for the rows whose A operands this lane supplies (one per tile)
+        int jr[T], ir[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) jr[t] = j0 + 16 * t + row16 < a.j_end ? j0 + 16 * t + row16 : n;
+        if (FROM_MASK) {
+            select_set_bits_lane<T>(a.words_lds, a.pre_lds, a.nwords, a.top_step, n, jr, ir);
+        } else {
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                ir[t] = jr[t] < n ? a.idx_in[jr[t]] : -1;
+                if ((unsigned)ir[t] >= (unsigned)a.ffn) ir[t] = -1;
+            }
+        }
+        if (wave == 0 && kg == 0) {
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                a.irow[16 * t + row16] = ir[t];
+                if (FROM_MASK && ir[t] >= 0) a.idx_out[jr[t]] = ir[t];
+            }
+        }
+        // byte offsets of the rows this lane fetches: instruction i -> row RPI * i + lane / LPR
+        uint32_t rowoff[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = RPI * i + lane / LPR;
+            int id = -1;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const int v = __shfl(ir[t], row & 15, 64);
+                if ((row >> 4) == t) id = v;
+            }
+            rowoff[i] = id >= 0 ? (uint32_t)id * (uint32_t)d * 2u : kOobOffset;
+        }
+        if (j0 == a.j_begin) PF_TSTAMP(2, 2);
+
+        float4v_t cu[T], cg[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            cu[t] = (float4v_t){0.f, 0.f, 0.f, 0.f};
+            cg[t] = (float4v_t){0.f, 0.f, 0.f, 0.f};
+        }
+        const int ntile = min(T, (a.j_end - j0 + 15) >> 4);  // block-uniform: tiles with rows
+        int c = wave;
+        if (c < nchunks) {
+            mfma_issue_chunk<R>(a.wu, slot, rowoff, c, d, lane);
+            if (GATED) mfma_issue_chunk<R>(a.wg, slot + kMfmaSlotBytes, rowoff, c, d, lane);
+        }
+        while (c < nchunks) {  // wave-uniform
+            float4 xa[STEPS], xb[STEPS];
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                const int k = c * KC + s * 32;
+                const uint32_t o = (k < d && xoff != kOobOffset) ? xoff + (uint32_t)k * 4u : kOobOffset;
+                xa[s] = ld16_f32(a.xr, o);
+                xb[s] = ld16_f32(a.xr, o != kOobOffset ? o + 16u : kOobOffset);
+            }
+            Half8Bits au[T][STEPS], ag[T][STEPS];
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                if (t >= ntile) break;
+#pragma unroll
+                for (int s = 0; s < STEPS; ++s) {
+                    const int row = 16 * t + row16;
+                    const int at = row * (KC * 2) + ((4 * s + kg) ^ (row & 7)) * 16;
+                    au[t][s].u = *reinterpret_cast<const uint4 *>(slot + at);
+                    if (GATED) ag[t][s].u = *reinterpret_cast<const uint4 *>(slot + kMfmaSlotBytes + at);
+                }
+            }
+            const int cn = c + kMfmaWaves;
+            if (cn < nchunks) {  // refill the slot once its contents are in the registers
+                __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+                mfma_issue_chunk<R>(a.wu, slot, rowoff, cn, d, lane);
+                if (GATED) mfma_issue_chunk<R>(a.wg, slot + kMfmaSlotBytes, rowoff, cn, d, lane);
+            }
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                half8_t hi, lo;
+                split_hi_lo(xa[s], xb[s], hi, lo);
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    if (t >= ntile) break;
+                    cu[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(au[t][s].h, hi, cu[t], 0, 0, 0);
+                    cu[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(au[t][s].h, lo, cu[t], 0, 0, 0);
+                    if (GATED) {
+                        cg[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ag[t][s].h, hi, cg[t], 0, 0, 0);
+                        cg[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ag[t][s].h, lo, cg[t], 0, 0, 0);
+                    }
+                }
+            }
+            c = cn;
+        }
+        if (j0 == a.j_begin) PF_TSTAMP(2, 3);
+        // this lane holds C[row 4*kg + e][col row16] of its chunks, per tile; the wave's slot
+        // is free now: [tile][up | gate][256]
+        float *ctile = reinterpret_cast<float *>(slot);
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                ctile[(t * 2) * 256 + (kg * 4 + e) * 16 + row16] = cu[t][e];
+                if (GATED) ctile[(t * 2 + 1) * 256 + (kg * 4 + e) * 16 + row16] = cg[t][e];
+            }
+        __syncthreads();
+        if ((int)threadIdx.x < T * 256) {
+            const int t = threadIdx.x >> 8, e = threadIdx.x & 255;
+            const int row = 16 * t + (e >> 4), colb = e & 15;
+            float su = 0.f, sg = 0.f;
+#pragma unroll
+            for (int wv = 0; wv < kMfmaWaves; ++wv) {
+                const float *ct = reinterpret_cast<const float *>(a.slots + (size_t)wv * NM * kMfmaSlotBytes);
+                su += ct[(t * 2) * 256 + e];
+                if (GATED) sg += ct[(t * 2 + 1) * 256 + e];
+            }
+            const int i = a.irow[row];
+            const int j = j0 + row;
+            const float bias = (a.b_up != nullptr && i >= 0) ? a.b_up[i] : 0.f;
+            const float v = GATED ? fmaxf(sg + bias, 0.f) * su : fmaxf(su + bias, 0.f);
+            if (colb < a.B && j < a.j_end) a.h[(size_t)j * a.hs + colb] = i >= 0 ? v : 0.f;
+        }
+        __syncthreads();
+        if (j0 == a.j_begin) PF_TSTAMP(2, 4);
+    }
+}
+
+// grid = G blocks; block b owns the list slots [b * rpb, (b + 1) * rpb), rpb = ceil(n / G): an
+// even share of the rows for every block (with whole tiles dealt round-robin the CUs that get
+// one tile more than the others set the kernel's time).  A share of at most 16 rows is done
+// as one 16-row tile with 256-element chunks, a larger one in passes of 32 rows (two tiles)
+// with 128-element chunks.  The 8 waves of a block take the chunks round-robin (wave w:
+// chunks w, w + 8, ...) for the same rows and their C tiles are added in LDS in wave order.
+// d % 32 == 0, B <= 16.
 template <int ACT, bool FROM_MASK>
 __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
@@ -98,18 +254,13 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
 {
     extern __shared__ uint64_t dyn_lds64[];
     __shared__ uint32_t wave_tot[kMfmaWaves];
-    __shared__ int irow[kMfmaRows];
+    __shared__ int irow[32];
     constexpr bool GATED = (ACT == 1);
-    constexpr int NM = GATED ? 2 : 1;
-    const int lane = threadIdx.x & 63, wave = wave_uniform(threadIdx.x >> 6);
-    const int row16 = lane & 15, kg = lane >> 4;
     const int nwords = ffn / 64;
     uint64_t *words_lds = dyn_lds64;
     uint32_t *pre_lds = reinterpret_cast<uint32_t *>(words_lds + (FROM_MASK ? nwords : 0));
     const size_t mask_bytes =
         FROM_MASK ? (((size_t)nwords * 8 + ((size_t)nwords + 1) * 4 + 63) / 64) * 64 : 0;
-    char *slots = reinterpret_cast<char *>(dyn_lds64) + mask_bytes;
-    char *slot = slots + (size_t)wave * NM * kMfmaSlotBytes;  // this wave's: up, then gate
 
     PF_TSTAMP(2, 0);
     int n;
@@ -121,132 +272,33 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     } else {
         n = min(max(*count_in, 0), ffn);
     }
-    const rsrc_t wu = make_rsrc(w_up, (uint32_t)ffn * (uint32_t)d * 2u);
-    const rsrc_t wg = make_rsrc(GATED ? w_gate : w_up, (uint32_t)ffn * (uint32_t)d * 2u);
-    const rsrc_t xr = make_rsrc(x, (uint32_t)B * (uint32_t)d * 4u);
-    const uint32_t xoff = row16 < B ? ((uint32_t)row16 * (uint32_t)d + (uint32_t)kg * 8u) * 4u : kOobOffset;
-    const int nchunks = (d + kMfmaKC - 1) / kMfmaKC;
+    UpMfmaArgs a;
+    a.wu = make_rsrc(w_up, (uint32_t)ffn * (uint32_t)d * 2u);
+    a.wg = make_rsrc(GATED ? w_gate : w_up, (uint32_t)ffn * (uint32_t)d * 2u);
+    a.xr = make_rsrc(x, (uint32_t)B * (uint32_t)d * 4u);
+    a.b_up = b_up;
+    a.idx_in = idx_in;
+    a.idx_out = idx_out;
+    a.h = h;
+    a.words_lds = words_lds;
+    a.pre_lds = pre_lds;
+    a.slots = reinterpret_cast<char *>(dyn_lds64) + mask_bytes;
+    a.irow = irow;
+    a.B = B;
+    a.hs = hs;
+    a.d = d;
+    a.ffn = ffn;
+    a.n = n;
+    a.nwords = nwords;
+    a.top_step = top_step;
     const int rpb = (n + (int)gridDim.x - 1) / (int)gridDim.x;
-    const int j_begin = min(n, (int)blockIdx.x * rpb), j_end = min(n, j_begin + rpb);
-    // this lane's A operands of tile t, K step s: row 16t + row16, piece 4s + kg
-    const int arow0 = row16 * (kMfmaKC * 2), aswz = mfma_swz(row16);  // swz(16 + r) == swz(r)
+    a.j_begin = min(n, (int)blockIdx.x * rpb);
+    a.j_end = min(n, a.j_begin + rpb);
     PF_TSTAMP(2, 1);
-
-    for (int j0 = j_begin; j0 < j_end; j0 += kMfmaRows) {
-        const bool two = j_end - j0 > 16;  // block-uniform: the second tile has rows
-        // list slot -> neuron id for the two rows whose A operands this lane supplies
-        const int jr[2] = {j0 + row16 < j_end ? j0 + row16 : n, j0 + 16 + row16 < j_end ? j0 + 16 + row16 : n};
-        int ir[2];
-        if (FROM_MASK) {
-            select_set_bits_lane<2>(words_lds, pre_lds, nwords, top_step, n, jr, ir);
-        } else {
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                ir[t] = jr[t] < n ? idx_in[jr[t]] : -1;
-                if ((unsigned)ir[t] >= (unsigned)ffn) ir[t] = -1;
-            }
-        }
-        if (wave == 0 && kg == 0) {
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                irow[16 * t + row16] = ir[t];
-                if (FROM_MASK && ir[t] >= 0) idx_out[jr[t]] = ir[t];
-            }
-        }
-        // byte offsets of the rows this lane fetches: instruction i -> row 4i + lane / 16
-        uint32_t rowoff[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int id = __shfl(ir[i >> 2], (4 * i + kg) & 15, 64);
-            rowoff[i] = id >= 0 ? (uint32_t)id * (uint32_t)d * 2u : kOobOffset;
-        }
-        if (j0 == j_begin) PF_TSTAMP(2, 2);
-
-        float4v_t cu[2], cg[2];
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            cu[t] = (float4v_t){0.f, 0.f, 0.f, 0.f};
-            cg[t] = (float4v_t){0.f, 0.f, 0.f, 0.f};
-        }
-        int c = wave;
-        if (c < nchunks) {
-            mfma_issue_chunk(wu, slot, rowoff, c, d, lane);
-            if (GATED) mfma_issue_chunk(wg, slot + kMfmaSlotBytes, rowoff, c, d, lane);
-        }
-        while (c < nchunks) {  // wave-uniform
-            float4 xa[kMfmaSteps], xb[kMfmaSteps];
-#pragma unroll
-            for (int s = 0; s < kMfmaSteps; ++s) {
-                const int k = c * kMfmaKC + s * 32;
-                const uint32_t o = (k < d && xoff != kOobOffset) ? xoff + (uint32_t)k * 4u : kOobOffset;
-                xa[s] = ld16_f32(xr, o);
-                xb[s] = ld16_f32(xr, o != kOobOffset ? o + 16u : kOobOffset);
-            }
-            Half8Bits au[2][kMfmaSteps], ag[2][kMfmaSteps];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                if (t == 1 && !two) break;
-#pragma unroll
-                for (int s = 0; s < kMfmaSteps; ++s) {
-                    const int at = t * 16 * (kMfmaKC * 2) + arow0 + ((4 * s + kg) ^ aswz) * 16;
-                    au[t][s].u = *reinterpret_cast<const uint4 *>(slot + at);
-                    if (GATED) ag[t][s].u = *reinterpret_cast<const uint4 *>(slot + kMfmaSlotBytes + at);
-                }
-            }
-            const int cn = c + kMfmaWaves;
-            if (cn < nchunks) {  // refill the slot once its contents are in the registers
-                __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-                mfma_issue_chunk(wu, slot, rowoff, cn, d, lane);
-                if (GATED) mfma_issue_chunk(wg, slot + kMfmaSlotBytes, rowoff, cn, d, lane);
-            }
-#pragma unroll
-            for (int s = 0; s < kMfmaSteps; ++s) {
-                half8_t hi, lo;
-                split_hi_lo(xa[s], xb[s], hi, lo);
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    if (t == 1 && !two) break;
-                    cu[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(au[t][s].h, hi, cu[t], 0, 0, 0);
-                    cu[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(au[t][s].h, lo, cu[t], 0, 0, 0);
-                    if (GATED) {
-                        cg[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ag[t][s].h, hi, cg[t], 0, 0, 0);
-                        cg[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ag[t][s].h, lo, cg[t], 0, 0, 0);
-                    }
-                }
-            }
-            c = cn;
-        }
-        if (j0 == j_begin) PF_TSTAMP(2, 3);
-        // this lane holds C[row 4*kg + e][col row16] of its chunks, per tile; the wave's slot
-        // is free now: [tile][up | gate][256]
-        float *ctile = reinterpret_cast<float *>(slot);
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                ctile[(t * 2) * 256 + (kg * 4 + e) * 16 + row16] = cu[t][e];
-                if (GATED) ctile[(t * 2 + 1) * 256 + (kg * 4 + e) * 16 + row16] = cg[t][e];
-            }
-        __syncthreads();
-        {
-            const int t = threadIdx.x >> 8, e = threadIdx.x & 255;
-            const int row = 16 * t + (e >> 4), colb = e & 15;
-            float su = 0.f, sg = 0.f;
-#pragma unroll
-            for (int wv = 0; wv < kMfmaWaves; ++wv) {
-                const float *ct = reinterpret_cast<const float *>(slots + (size_t)wv * NM * kMfmaSlotBytes);
-                su += ct[(t * 2) * 256 + e];
-                if (GATED) sg += ct[(t * 2 + 1) * 256 + e];
-            }
-            const int i = irow[row];
-            const int j = j0 + row;
-            const float bias = (b_up != nullptr && i >= 0) ? b_up[i] : 0.f;
-            const float v = GATED ? fmaxf(sg + bias, 0.f) * su : fmaxf(su + bias, 0.f);
-            if (colb < B && j < j_end) h[(size_t)j * hs + colb] = i >= 0 ? v : 0.f;
-        }
-        __syncthreads();
-        if (j0 == j_begin) PF_TSTAMP(2, 4);
-    }
+    if (rpb <= 16)
+        up_mfma_passes<16, ACT, FROM_MASK>(a);
+    else
+        up_mfma_passes<32, ACT, FROM_MASK>(a);
     PF_TSTAMP(2, 5);
 }
 

@@ -40,7 +40,7 @@ struct pf_ctx {
     int num_cu = 256;
     int up_grid_cap = 2048;
     int up_grid_cap_i4 = 512;
-    int mfma_grid = 256;
+    int mfma_grid = 0;              // PF_MFMA_GRID: blocks of k_up_mfma (0 = from the CU count)
     // The hidden layer goes to the matrix cores only above this B * d: below it the vector kernel
     // with the glue fused in beats MFMA + a glue kernel of its own (measured: +1..3 % on the
     // stack at 4 x 4096 and 4 x 5120, -9 % and worse from 8 x 4096 on).
@@ -401,7 +401,9 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     const size_t mfma_lds = pf::up_mfma_lds_bytes(D.ffn, from_mask, gated);
     const bool mfma = B >= ctx->mfma_min_batch && D.d % 32 == 0 && mfma_lds <= (size_t)ctx->lds_budget;
     if (mfma) {  // the whole batch in one launch: tokens are the N columns of the tile
-        const int grid = ctx->mfma_grid;  // one block per CU (its LDS image fills the CU)
+        // one block per CU: a block's fixed cost (mask scan, bit select, tile reduction) is about
+        // 7 us, so two rounds of smaller blocks lose more than their longer chunks gain
+        const int grid = ctx->mfma_grid > 0 ? ctx->mfma_grid : ctx->num_cu;
         ProfScope ps(ctx, K_UP_MFMA);
 #define PF_UPM(ACT, FM)                                                                           \
     PF_LAUNCH(ps, (pf::k_up_mfma<ACT, FM>), dim3(grid), dim3(pf::kMfmaThreads), mfma_lds, st, w_up, \
@@ -639,7 +641,7 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         if (prop.multiProcessorCount > 0) ctx->num_cu = prop.multiProcessorCount;
         ctx->up_grid_cap = 8 * ctx->num_cu;
         ctx->up_grid_cap_i4 = 2 * ctx->num_cu;
-        ctx->mfma_grid = ctx->num_cu;
+        ctx->mfma_grid = 0;  // 0: from the CU count
         if (const char *v = getenv("PF_HIDDEN_MFMA_MIN_ELEMS")) ctx->hidden_mfma_min_elems = atoi(v);
         if (const char *v = getenv("PF_MFMA_GRID")) {
             int c = atoi(v);
