@@ -49,6 +49,8 @@ def parse_args():
     ap.add_argument("--lookahead", type=int, default=0, choices=[0, 1],
                     help="1: look-ahead prediction at distance 1 (predictors overlap the sparse "
                          "kernels of the layer before; lists differ from the default path)")
+    ap.add_argument("--rank", type=int, default=None,
+                    help="override the predictor rank r of every layer (a multiple of 8)")
     ap.add_argument("--rate", type=float, default=None,
                     help="override the configuration's mean activation rate (scaling runs)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "pmc_traffic.json"),
@@ -134,6 +136,8 @@ def main():
         cfg = wl.scaled(cfg, layers=args.layers)
     if args.rate is not None:
         cfg = wl.scaled(cfg, rate=args.rate)
+    if args.rank is not None:
+        cfg = wl.scaled(cfg, r=args.rank)
     B = args.batch
     K = args.steps if args.steps is not None else cfg.tokens
     W = args.warmup

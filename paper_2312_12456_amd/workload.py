@@ -80,6 +80,10 @@ CONFIGS = {
                            0.06, 1.3, 256, (1, 4, 8)),
     "opt-175b-int4": StackConfig("opt-175b-int4", 96, 12288, 49152, 2048, ACT_RELU,
                                  W_INT4_G128, 0.04, 1.3, 256, (1,)),
+    # a second OPT-like shape beside the benchmark configurations: the ReLU Falcon-40B FFN
+    # (95 % sparsity in the paper's model table), 60 layers
+    "falcon-40b-relu": StackConfig("falcon-40b-relu", 60, 8192, 32768, 1024, ACT_RELU, W_FP16,
+                                   0.05, 1.2, 256, (1,)),
 }
 
 

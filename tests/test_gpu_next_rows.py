@@ -163,3 +163,40 @@ def test_stack_lookahead_matches_oracle(pf, act, B):
     assert torch.equal(again, plain)
     with pytest.raises(pf.PfError):
         ctx.set_lookahead(2)
+
+
+def test_stack_with_a_different_predictor_rank_per_layer(pf):
+    """Non-fixed-size predictors (PowerInfer Sec. 5.1: the hidden width of each layer's
+    predictor is tuned to the layer): a stack whose layers have ranks 64, 136 and 264 in one
+    context.  Every layer is checked against the oracle on the oracle's own input (teacher
+    forced), and the stack call against the chain of stand-alone calls."""
+    from oracle import pf_oracle
+    ranks = [64, 136, 264]
+    base = small_cfg(d=520, ffn=1344, r=max(ranks), rate=0.1, layers=len(ranks))
+    cfgs = [wl.scaled(base, r=r) for r in ranks]
+    lays = [wl.make_layer(c, l, 51, device="cuda") for l, c in enumerate(cfgs)]
+    ctx = pf.Context(base.d, base.ffn, max(ranks), max_batch=2)
+    Ls = [pf.Layer.from_workload(ctx, c, t) for c, t in zip(cfgs, lays)]
+    Os = [oracle_layer(c, wl.to_host(t)) for c, t in zip(cfgs, lays)]
+    x = wl.make_inputs(base, 0, seed=51, batch=2, device="cuda")
+    xo = x.cpu().numpy()
+    xc, yc = x.clone(), torch.empty_like(x)
+    for L, O, c in zip(Ls, Os, cfgs):
+        xg = torch.from_numpy(xo).cuda()
+        y = torch.empty_like(xg)
+        ctx.layer_step(L, xg, y)
+        torch.cuda.synchronize()
+        wptr, lst = _last_list(pf, ctx, c.ffn)
+        sc = O.predict(xo)["scores"]
+        mask = np.zeros(c.ffn, bool)
+        mask[lst] = True
+        decided = (np.abs(sc - c.threshold) >= 1e-3).all(axis=0)
+        assert np.array_equal(mask[decided], (sc > c.threshold).any(axis=0)[decided])
+        check_output(y.cpu().numpy(), O.masked_ffn(xo, mask), "rank %d" % c.r)
+        xo = pf_oracle.stack_glue(xo, O.masked_ffn(xo, mask))
+        ctx.layer_step(L, xc, yc)
+        ctx.stack_glue(xc, yc, xc)
+    out = torch.empty_like(x)
+    ctx.stack_step(Ls, x, out)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out.cpu().numpy(), xc.cpu().numpy(), atol=1e-4, rtol=0)
