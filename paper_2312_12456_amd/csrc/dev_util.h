@@ -137,11 +137,7 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
 // 16-byte streaming load (weights are read once per token: no reuse to keep in cache).
 __device__ __forceinline__ uint4 ld16_stream(rsrc_t r, uint32_t byte_off)
 {
-#ifndef PF_PLAIN_LOADS
     const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 2);  // nt
-#else
-    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
-#endif
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 

@@ -149,10 +149,7 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
 // NB*g on (NB = 16, 32 or 64: a quarter, half or whole mask word), wave w of it rows
 // 4w .. 4w+3, all in flight at once; wave 0 turns the NB decisions into its piece of the
 // mask word with a ballot.
-#ifndef PF_OUT_NEURONS
-#define PF_OUT_NEURONS 64
-#endif
-constexpr int kPredOutNeurons = PF_OUT_NEURONS;
+constexpr int kPredOutNeurons = 64;
 constexpr int kPredOutThreads = kPredOutNeurons * 16;
 static_assert(kPredOutNeurons == 16 || kPredOutNeurons == 32 || kPredOutNeurons == 64, "mask piece");
 template <int NB> struct MaskPiece { typedef uint64_t type; };
@@ -178,15 +175,13 @@ __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
 
     PF_TSTAMP(1, 0);
     stage_dma<B>(ts, t, r, kpad);
-#ifndef PF_OUT_PRE
-#define PF_OUT_PRE 2  // rows whose loads are issued before the block barrier
-#endif
+    constexpr int PRE = 2;  // rows whose loads are issued before the block barrier
     WGroup<U> g[R];
 #pragma unroll
-    for (int q = 0; q < PF_OUT_PRE; ++q) load_group<U>(g[q], rows[q], 0, lane);
+    for (int q = 0; q < PRE; ++q) load_group<U>(g[q], rows[q], 0, lane);
     __syncthreads();
 #pragma unroll
-    for (int q = PF_OUT_PRE; q < R; ++q) load_group<U>(g[q], rows[q], 0, lane);
+    for (int q = PRE; q < R; ++q) load_group<U>(g[q], rows[q], 0, lane);
     PF_TSTAMP(1, 1);
 
     float acc[R][B];
