@@ -25,7 +25,9 @@ constexpr int kPredWaves = kPredThreads / kWave;
 // yp may arrive as ny <= 4 partial sums, ypstride floats apart (row-split FC2): they are
 // added in the fixed order 0 .. ny-1.  b0 = batch row of the first token this launch handles
 // (the glue's sign pattern depends on the row).
-template <int B, bool GLUE>
+// GS = strides of 1024 elements whose glue loads (x and up to 4 partial sums each) a thread
+// issues together: 4 covers d <= 4096 in a single round trip, at 80 registers.
+template <int B, bool GLUE, int GS = (B >= 2 ? 1 : 2)>
 __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__restrict__ p1,
                                                               const float *__restrict__ x,
                                                               const float *__restrict__ yp, int ny,
@@ -51,7 +53,7 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
         float ss[B];
 #pragma unroll
         for (int b = 0; b < B; ++b) ss[b] = 0.f;
-        constexpr int S = (B >= 2) ? 1 : 2;  // strides whose loads are issued together
+        constexpr int S = GS;  // strides whose loads are issued together
         constexpr int step = kPredThreads * 4;
         bool issued = false;
         const rsrc_t xr = make_rsrc(x, (uint32_t)B * (uint32_t)d * 4u);

@@ -149,6 +149,7 @@ template <int B>
 hipError_t allow_lds_for_batch()
 {
     hipError_t e = allow_lds(pf::k_pred_hidden<B, false>);
+    if (e == hipSuccess && B == 1) e = allow_lds(pf::k_pred_hidden<1, true, 4>);
     if (e == hipSuccess) e = allow_lds(pf::k_pred_hidden<B, true>);
     if (e == hipSuccess) e = allow_lds(pf::k_up<B, 0, false>);
     if (e == hipSuccess) e = allow_lds(pf::k_up<B, 1, false>);
@@ -266,7 +267,11 @@ pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const fl
         const dim3 grid(cdiv(D.r, pf::kPredWaves));
         const size_t xo = (size_t)b0 * D.d;
         ProfScope ps(ctx, K_PRED_HIDDEN);
-        if (glue_y) {
+        if (glue_y && bt == 1 && kpad_of(D.d) <= 4096) {  // the whole glue in one round trip
+            PF_LAUNCH(ps, (pf::k_pred_hidden<1, true, 4>), grid, dim3(pf::kPredThreads), lds, st, p1,
+                      x + xo, glue_y + xo, glue_ny, B * D.d, x_new + xo, ctx->t + (size_t)b0 * D.r, D.d,
+                      D.r, b0);
+        } else if (glue_y) {
             PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_pred_hidden<BT, true>), grid,
                                                dim3(pf::kPredThreads), lds, st, p1, x + xo,
                                                glue_y + xo, glue_ny, B * D.d, x_new + xo,
