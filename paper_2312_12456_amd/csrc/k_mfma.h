@@ -92,6 +92,7 @@ struct UpMfmaArgs {
     const uint32_t *pre_lds;
     char *slots;
     int *irow;
+    float *brow;
     int B, hs, d, ffn, n, nwords, top_step, j_begin, j_end;
 };
 
@@ -130,6 +131,7 @@ __device__ __forceinline__ void up_mfma_passes(const UpMfmaArgs &a)
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 a.irow[16 * t + row16] = ir[t];
+                a.brow[16 * t + row16] = (a.b_up != nullptr && ir[t] >= 0) ? a.b_up[ir[t]] : 0.f;
                 if (FROM_MASK && ir[t] >= 0) a.idx_out[jr[t]] = ir[t];
             }
         }
@@ -228,7 +230,7 @@ __device__ __forceinline__ void up_mfma_passes(const UpMfmaArgs &a)
             }
             const int i = a.irow[row];
             const int j = j0 + row;
-            const float bias = (a.b_up != nullptr && i >= 0) ? a.b_up[i] : 0.f;
+            const float bias = a.brow[row];  // fetched when the row was selected
             const float v = GATED ? fmaxf(sg + bias, 0.f) * su : fmaxf(su + bias, 0.f);
             if (colb < a.B && j < a.j_end) a.h[(size_t)j * a.hs + colb] = i >= 0 ? v : 0.f;
         }
@@ -255,6 +257,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     extern __shared__ uint64_t dyn_lds64[];
     __shared__ uint32_t wave_tot[kMfmaWaves];
     __shared__ int irow[32];
+    __shared__ float brow[32];
     constexpr bool GATED = (ACT == 1);
     const int nwords = ffn / 64;
     uint64_t *words_lds = dyn_lds64;
@@ -284,6 +287,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     a.pre_lds = pre_lds;
     a.slots = reinterpret_cast<char *>(dyn_lds64) + mask_bytes;
     a.irow = irow;
+    a.brow = brow;
     a.B = B;
     a.hs = hs;
     a.d = d;
