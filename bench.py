@@ -264,9 +264,10 @@ def main():
         "alg_bytes_per_launch": dk["alg_bytes"], "avg_us": dk["avg_us"],
     }
     touched = k_mean * nm * cfg.row_bytes
+    # FC1 + FC2.  (k_combine, which adds FC2's partial sums for a stand-alone layer step, is
+    # not part of the stack: there the next layer's first kernel adds them while it forms x.)
     up_name = "k_up_mfma" if "k_up_mfma" in kernels else "k_up"
-    t_sparse_us = kernels[up_name]["avg_us"] + kernels["k_down"]["avg_us"] + \
-        kernels.get("k_combine", {"avg_us": 0.0})["avg_us"]
+    t_sparse_us = kernels[up_name]["avg_us"] + kernels["k_down"]["avg_us"]
     touched_gbps = touched / (t_sparse_us * 1e-6) / 1e9
 
     # ---- CPU oracle on the host cores, bounded sample --------------------------------
