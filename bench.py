@@ -269,6 +269,14 @@ def main():
     up_name = "k_up_mfma" if "k_up_mfma" in kernels else "k_up"
     t_sparse_us = kernels[up_name]["avg_us"] + kernels["k_down"]["avg_us"]
     touched_gbps = touched / (t_sparse_us * 1e-6) / 1e9
+    # layer level: every algorithmic byte of a layer over the layer's share of the step time
+    pred_bytes = alg_bytes["k_pred_hidden"] + alg_bytes["k_pred_out"]
+    layer_us = 1e3 * ms_per_step / cfg.layers
+    layer = {"bytes_per_layer": pred_bytes + touched, "us_per_layer": round(layer_us, 3),
+             "GBps": round((pred_bytes + touched) / (layer_us * 1e-6) / 1e9, 1),
+             "frac_of_peak": round((pred_bytes + touched) / (layer_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+             "touched_only_GBps": round(touched / (layer_us * 1e-6) / 1e9, 1),
+             "touched_only_ceiling": round(touched / (pred_bytes + touched), 4)}
 
     # ---- CPU oracle on the host cores, bounded sample --------------------------------
     cpu = None
@@ -324,6 +332,7 @@ def main():
         "touched": {"k_mean": round(k_mean, 1), "active_frac": round(k_mean / cfg.ffn, 4),
                     "bytes_per_layer": touched, "sparse_us_per_layer": round(t_sparse_us, 3),
                     "GBps": round(touched_gbps, 1), "frac_of_peak": round(touched_gbps / HBM_PEAK_GBPS, 4)},
+        "layer": layer,
         "latency": latency,
         "kernels": kernels,
         "setup_s": round(t_gen, 1),
