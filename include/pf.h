@@ -80,7 +80,14 @@ typedef struct pf_ctx pf_ctx;
 typedef struct pf_layer pf_layer;
 typedef struct pf_plan pf_plan;
 
-/* Context: binds a device and owns scratch sized for the given maxima (hidden vector,
+/* Arithmetic (Sec. 8.1: fp16 or int4 weights, fp32 activations): every product is accumulated
+ * in fp32.  Batches of 1 to 3 tokens multiply fp32 activations with the widened weights on the
+ * vector units.  From 4 tokens on FC1 and the predictor run on the matrix cores, where each
+ * fp32 activation enters as the sum of two fp16 numbers (rounded value + residual, 21 bits
+ * kept); activations there must lie inside the fp16 range (|x| < 65504), which normalised
+ * hidden states do by orders of magnitude.
+ *
+ * Context: binds a device and owns scratch sized for the given maxima (hidden vector,
  * mask words, index list, FC1 outputs, FC2 partial sums).  `device` is a HIP ordinal.
  * Errors: PF_EINVAL (out == NULL, sizes < 1, max_batch > 8), PF_ESHAPE, PF_ENOMEM, PF_EHIP. */
 pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int max_r,
