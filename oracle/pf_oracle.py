@@ -23,8 +23,25 @@ W_FP16 = 0
 W_INT4_G128 = 1
 
 
+def build_checked():
+    """A second build with the undefined-behaviour sanitizer trapping on the first finding
+    (signed overflow, misaligned or out-of-bounds access the compiler can see, bad shifts):
+    oracle/libpf_oracle_ubsan.so.  PF_ORACLE_LIB selects it for a test run."""
+    out = os.path.join(_HERE, "libpf_oracle_ubsan.so")
+    tmp = out + ".tmp.%d" % os.getpid()
+    subprocess.check_call(
+        ["gcc", "-O1", "-g", "-std=c99", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+         "-fsanitize=undefined", "-fsanitize-undefined-trap-on-error", "-fno-sanitize-recover=all",
+         "-o", tmp, _SRC, "-lm"])
+    os.replace(tmp, out)
+    return out
+
+
 def build(force=False):
     """Compile pf_oracle.c with gcc into oracle/libpf_oracle.so."""
+    override = os.environ.get("PF_ORACLE_LIB")
+    if override:
+        return override
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(

@@ -200,3 +200,34 @@ def test_stack_with_a_different_predictor_rank_per_layer(pf):
     ctx.stack_step(Ls, x, out)
     torch.cuda.synchronize()
     np.testing.assert_allclose(out.cpu().numpy(), xc.cpu().numpy(), atol=1e-4, rtol=0)
+
+
+@pytest.mark.parametrize("B", [1, 3, 8])
+def test_repeated_runs_are_bit_identical(pf, B):
+    """No atomics, one owner and one order for every sum: the same step twice (eagerly and as a
+    replayed plan) gives the same bits, on the vector path (B = 1, 3) and on the matrix cores
+    (B = 8).  A race between workgroups would show up here."""
+    cfg = small_cfg(d=2056, ffn=2048, r=264, rate=0.15, layers=3)
+    lays = [wl.make_layer(cfg, l, 61, device="cuda") for l in range(cfg.layers)]
+    ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
+    Ls = [pf.Layer.from_workload(ctx, cfg, t) for t in lays]
+    x = wl.make_inputs(cfg, 0, seed=61, batch=B, device="cuda")
+    first = torch.empty_like(x)
+    ctx.stack_step(Ls, x, first)
+    torch.cuda.synchronize()
+    out = torch.empty_like(x)
+    plan = pf.Plan(ctx, Ls, x, out)
+    for rep in range(5):
+        again = torch.full_like(x, float("nan"))
+        ctx.stack_step(Ls, x, again)
+        out.fill_(float("nan"))
+        plan.run()
+        torch.cuda.synchronize()
+        assert torch.equal(again, first), "eager repeat %d differs" % rep
+        assert torch.equal(out, first), "plan replay %d differs" % rep
+    plan.close()
+    y1, y2 = torch.empty_like(x), torch.empty_like(x)
+    ctx.layer_step(Ls[0], x, y1)
+    ctx.layer_step(Ls[0], x, y2)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)

@@ -463,3 +463,20 @@ def test_stack_lookahead_reads_the_previous_layers_input(oracle):
     o1, m1 = oracle.stack_lookahead(layers[:1], x0)
     assert np.array_equal(m1[0], m)
     np.testing.assert_array_equal(o1, oracle.stack_glue(x0, y))
+
+
+def test_oracle_is_clean_under_the_undefined_behaviour_sanitizer():
+    """The identities, the brute-force enumeration and the int4 cases once more against a build
+    of the oracle that traps on undefined behaviour (a crash of the child = a finding)."""
+    import subprocess
+    import sys
+    from oracle import pf_oracle
+    lib = pf_oracle.build_checked()
+    env = dict(os.environ, PF_ORACLE_LIB=lib)
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-m", "pytest", "-q", "-x", "-p", "no:cacheprovider",
+                        os.path.join(root, "tests", "test_oracle_pins.py"), "-k",
+                        "mask_identities or brute or int4 or half_to_double or stack_glue or lookahead"],
+                       cwd=root, env=env, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+    assert " passed" in r.stdout
