@@ -17,6 +17,7 @@
 #include "k_sparse.h"
 #include "k_int4.h"
 #include "k_mfma.h"
+#include "k_fused.h"
 
 namespace {
 
@@ -27,10 +28,12 @@ constexpr int kLdsMax = 160 * 1024;     // LDS per workgroup on gfx950
 constexpr int kLdsDefault = 64 * 1024;  // what a kernel may use without opting in
 
 enum KernelId {
-    K_PRED_HIDDEN = 0, K_PRED_OUT, K_COMPACT, K_UP, K_DOWN, K_GLUE, K_UP_MFMA, K_COMBINE, K_NUM
+    K_PRED_HIDDEN = 0, K_PRED_OUT, K_COMPACT, K_UP, K_DOWN, K_GLUE, K_UP_MFMA, K_COMBINE, K_OUT_UP,
+    K_DOWN_MASK, K_NUM
 };
 const char *const kKernelNames[K_NUM] = {"k_pred_hidden", "k_pred_out", "k_compact", "k_up",
-                                         "k_down",        "k_glue",     "k_up_mfma",  "k_combine"};
+                                         "k_down",        "k_glue",     "k_up_mfma",  "k_combine",
+                                         "k_out_up",      "k_down_mask"};
 
 }  // namespace
 
@@ -48,6 +51,9 @@ struct pf_ctx {
     int lds_budget = kLdsDefault;  // dynamic LDS a kernel of this context may request
     int down_split = 0;            // PF_DOWN_SPLIT: row groups of FC2 (0 = from the CU count)
     int mfma_min_batch = 4;        // FC1 goes to the matrix cores from this batch size on
+    int fused = 1;                 // PF_FUSED: inner layers of a stack as three launches (0 never,
+                                   // 1 where measured faster, 2 wherever possible)
+    int seg_strided = 0;           // PF_SEG_STRIDED: strided segments (models stored hot-first)
     // scratch (device)
     float *t = nullptr;              // [max_batch][max_r] predictor hidden vector
     uint64_t *mask_words = nullptr;  // [max_ffn / 64]
@@ -159,6 +165,8 @@ hipError_t allow_lds_for_batch()
     if (e == hipSuccess) e = allow_lds(pf::k_up_i4<B, 1, false>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_i4<B, 0, true>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_i4<B, 1, true>);
+    if (e == hipSuccess) e = allow_lds(pf::k_out_up<B, 0>);
+    if (e == hipSuccess) e = allow_lds(pf::k_out_up<B, 1>);
     return e;
 }
 
@@ -477,6 +485,72 @@ pf_status launch_layer(pf_ctx *ctx, const pf_layer *L, const float *x, const flo
     return launch_sparse(ctx, L, x_in, B, nullptr, nullptr, ctx->mask_words, y, ny_out, st);
 }
 
+// Whether the three-launch form of the layer step applies: fp16 weights, the vector path
+// (below the batch of the matrix-core kernels), and hidden vector + layer input of the whole
+// batch fit LDS.
+bool fused_ok(const pf_ctx *ctx, const pf_layer *L, int B)
+{
+    const pf_layer_desc &D = L->desc;
+    if (!ctx->fused || D.wtype == PF_W_INT4_G128 || B >= ctx->mfma_min_batch || B > 3 ||
+        pf::out_up_lds_bytes(B, D.r, D.d) + 1024 > (size_t)ctx->lds_budget)
+        return false;
+    if (ctx->fused > 1) return true;  // forced
+    // Measured on the five benchmark shapes: the fused form wins by 8 - 20 % where the saved
+    // kernel boundary weighs most (short rows, or three tokens, whose list-based kernels are
+    // slow) and loses 1 - 7 % with long rows at batch 1, where FC1 and FC2 are long enough
+    // for the uneven work per segment to cost more than the boundary.
+    const bool gated = D.act == PF_ACT_REGLU;
+    return B == 3 || D.d <= 4096 || (B == 2 && !gated);
+}
+
+// Layer step in three launches: hidden layer, output layer + FC1 per mask word, FC2 over the
+// mask words.  Leaves the mask but no index list; FC2's output stays as *ny_out partial sums.
+pf_status launch_layer_fused(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
+                             int glue_ny, float *x_new, int B, int *ny_out, hipStream_t st)
+{
+    const float *x_in = glue_y ? x_new : x;
+    pf_status s = launch_hidden(ctx, L, x, glue_y, glue_ny, x_new, B, st);
+    if (s != PF_OK) return s;
+    const pf_layer_desc &D = L->desc;
+    const __half *p2 = static_cast<const __half *>(L->w.p2);
+    const __half *w_up = static_cast<const __half *>(L->w.w_up);
+    const __half *w_gate = static_cast<const __half *>(L->w.w_gate);
+    const __half *w_down = static_cast<const __half *>(L->w.w_down);
+    const bool gated = D.act == PF_ACT_REGLU;
+    const size_t lds = pf::out_up_lds_bytes(B, D.r, D.d);
+    {
+        ProfScope ps(ctx, K_OUT_UP);
+#define PF_OU(ACT)                                                                                \
+    PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_out_up<BT, ACT>), dim3(D.ffn / 64),                       \
+                             dim3(pf::kPredOutThreads), lds, st, p2, L->w.p_bias,                 \
+                             (const float *)ctx->t, w_up, w_gate, L->w.b_up, x_in, D.r, D.d,      \
+                             D.ffn, pf::h_stride(B), L->thr_logit, ctx->seg_strided != 0,         \
+                             ctx->mask_words2,                                                    \
+                             reinterpret_cast<uint8_t *>(ctx->idx), ctx->h))
+        if (gated) { PF_OU(1); } else { PF_OU(0); }
+#undef PF_OU
+    }
+    const int tiles = cdiv(D.d, pf::kDown2Cols);
+    int P = ctx->down_split > 0 ? ctx->down_split : ctx->num_cu / tiles;
+    if (P < 1) P = 1;
+    if (P > pf::kDown2MaxSplit) P = pf::kDown2MaxSplit;
+    {
+        ProfScope ps(ctx, K_DOWN_MASK);
+        const bool multi = cdiv(D.ffn / 64, 8 * P) > pf::down2m_batch(B);
+#define PF_DM(MULTI)                                                                              \
+    PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_down2m<BT, MULTI>), dim3(tiles, P),                       \
+                             dim3(pf::kDown2Threads), 0, st, w_down, L->w.b_down,                 \
+                             (const float *)ctx->h, (const uint64_t *)ctx->mask_words2,           \
+                             reinterpret_cast<const uint8_t *>(ctx->idx), ctx->ypart, D.d, D.ffn, \
+                             ctx->seg_strided != 0))
+        if (multi) { PF_DM(true); } else { PF_DM(false); }
+#undef PF_DM
+    }
+    *ny_out = P;
+    PF_HIP(ctx, hipGetLastError());
+    return PF_OK;
+}
+
 pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int ny, int d, int B,
                       float *x_next, hipStream_t st)
 {
@@ -565,13 +639,15 @@ pf_status stack_enqueue(pf_ctx *ctx, pf_layer *const *layers, int n_layers, cons
     for (int l = 0; l < n_layers; ++l) {
         const pf_layer *L = layers[l];
         pf_status s;
-        if (l == 0) {
-            s = launch_layer(ctx, L, cur, nullptr, 0, nullptr, B, nullptr, &ny, st);
-        } else {
-            float *xn = ctx->xbuf[l & 1];
-            s = launch_layer(ctx, L, cur, ctx->ypart, ny, xn, B, nullptr, &ny, st);
-            cur = xn;
-        }
+        // the last layer always builds its index list (pf_ctx_last_active, pf_count_activations)
+        const bool fused = l + 1 < n_layers && fused_ok(ctx, L, B);
+        const float *gy = l == 0 ? nullptr : ctx->ypart;
+        float *xn = l == 0 ? nullptr : ctx->xbuf[l & 1];
+        if (fused)
+            s = launch_layer_fused(ctx, L, cur, gy, ny, xn, B, &ny, st);
+        else
+            s = launch_layer(ctx, L, cur, gy, l == 0 ? 0 : ny, xn, B, nullptr, &ny, st);
+        if (l > 0) cur = xn;
         if (s != PF_OK) return s;
     }
     return launch_glue(ctx, cur, ctx->ypart, ny, layers[0]->desc.d, B, x_out, st);
@@ -648,6 +724,8 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         ctx->up_grid_cap_i4 = 2 * ctx->num_cu;
         ctx->mfma_grid = 0;  // 0: from the CU count
         if (const char *v = getenv("PF_HIDDEN_MFMA_MIN_ELEMS")) ctx->hidden_mfma_min_elems = atoi(v);
+        if (const char *v = getenv("PF_FUSED")) ctx->fused = atoi(v);
+        if (const char *v = getenv("PF_SEG_STRIDED")) ctx->seg_strided = atoi(v) != 0;
         if (const char *v = getenv("PF_MFMA_GRID")) {
             int c = atoi(v);
             if (c >= 1 && c <= 65535) ctx->mfma_grid = c;
