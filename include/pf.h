@@ -182,7 +182,11 @@ pf_status pf_stack_glue(pf_ctx *ctx, const float *x, const float *y, int d, int 
 
 /* One decode step of a whole FFN stack: for each layer, pf_layer_step then pf_stack_glue.
  * layers: HOST array of n_layers layer handles of equal d.  x [B][d] in, x_out [B][d]
- * out (may alias x). */
+ * out (may alias x).  Up to batch 3 the layers before the last may run the same computation
+ * in three launches (predictor output layer and FC1 fused per 64 neurons, FC2 over those
+ * segments; no index list is built): same active sets bit for bit, FC2 summed in another
+ * fixed order.  pf_ctx_last_active after a stack step refers to the last layer, which always
+ * runs as pf_layer_step. */
 pf_status pf_stack_step(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x,
                         int B, float *x_out, void *stream);
 
