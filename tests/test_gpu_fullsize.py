@@ -90,3 +90,39 @@ def test_full_shape_stack_plan_matches_layer_chain(pf):
         np.testing.assert_allclose(out.cpu().numpy(), xc.cpu().numpy(), atol=1e-4, rtol=0)
         _ = (x0 + 1).sum().item()
     plan.close()
+
+
+@pytest.mark.parametrize("name,B", [("opt-6.7b", 1), ("opt-6.7b", 3), ("llama2-13b-reglu", 3)])
+def test_full_shape_stack_three_launch_form_matches_oracle(pf, oracle, name, B):
+    """Three full-size layers through the recorded plan, at the shapes and batches where the
+    stack's inner layers take the three-launch form (output layer + FC1 fused, FC2 over
+    segments): the oracle's stack, the list-form chain, and the launch counts."""
+    cfg = wl.scaled(wl.CONFIGS[name], layers=3)
+    ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
+    lays = [wl.make_layer(cfg, l, seed=2312, device="cuda") for l in range(cfg.layers)]
+    Ls = [pf.Layer.from_workload(ctx, cfg, t) for t in lays]
+    x0 = wl.make_inputs(cfg, 1, seed=2312, batch=B, device="cuda")
+    out = torch.full_like(x0, float("nan"))
+    plan = pf.Plan(ctx, Ls, x0, out)
+    plan.run()
+    torch.cuda.synchronize()
+    plan.close()
+    eager = torch.empty_like(x0)
+    ctx.profile_begin()
+    ctx.stack_step(Ls, x0, eager)
+    stats = ctx.profile_end()
+    assert stats["k_out_up"][0] == 2 and stats["k_down_mask"][0] == 2, stats
+    assert torch.equal(eager, out)
+    xc, yc = x0.clone(), torch.empty_like(x0)
+    for L in Ls:
+        ctx.layer_step(L, xc, yc)
+        ctx.stack_glue(xc, yc, xc)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out.cpu().numpy(), xc.cpu().numpy(), atol=2e-4, rtol=0)
+    xo, in_band = x0.cpu().numpy(), 0
+    for t in lays:
+        O = oracle_layer(cfg, wl.to_host(t))
+        in_band += int((np.abs(O.predict(xo)["scores"] - cfg.threshold) < 1e-3).sum())
+        xo = oracle.stack_glue(xo, O.layer_step(xo))
+    if in_band == 0:  # otherwise the active sets may differ legitimately
+        check_output(out.cpu().numpy(), xo, name + " three-launch stack")
