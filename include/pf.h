@@ -81,8 +81,9 @@ typedef struct pf_layer pf_layer;
 typedef struct pf_plan pf_plan;
 
 /* Arithmetic (Sec. 8.1: fp16 or int4 weights, fp32 activations): every product is accumulated
- * in fp32.  Batches of 1 to 3 tokens multiply fp32 activations with the widened weights on the
- * vector units.  From 4 tokens on FC1 and the predictor run on the matrix cores, where each
+ * in fp32.  Small batches multiply fp32 activations with the widened weights on the vector
+ * units.  From 4 tokens on -- from 3 where d > 4096 -- FC1 and the predictor of fp16 layers
+ * run on the matrix cores, where each
  * fp32 activation enters as the sum of two fp16 numbers (rounded value + residual, 21 bits
  * kept); activations there must lie inside the fp16 range (|x| < 65504), which normalised
  * hidden states do by orders of magnitude.

@@ -51,6 +51,7 @@ struct pf_ctx {
     int lds_budget = kLdsDefault;  // dynamic LDS a kernel of this context may request
     int down_split = 0;            // PF_DOWN_SPLIT: row groups of FC2 (0 = from the CU count)
     int mfma_min_batch = 4;        // FC1 goes to the matrix cores from this batch size on
+    bool mfma_min_batch_forced = false;  // set through PF_MFMA_MIN_B
     int fused = 1;                 // PF_FUSED: inner layers of a stack as three launches (0 never,
                                    // 1 where measured faster, 2 wherever possible)
     int seg_strided = 0;           // PF_SEG_STRIDED: strided segments (models stored hot-first)
@@ -238,11 +239,20 @@ struct ProfScope {
 pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int ny, int d, int B,
                       float *x_next, hipStream_t st);
 
+// Batch size from which a layer's kernels run on the matrix cores: 4, and already 3 for rows
+// longer than 4096 (measured at batch 3: OPT-30B shape 1 001 against 925 tokens/s, LLaMA-13B
+// shape 1 439 against 1 409, but OPT-6.7B shape 2 557 against 3 042); PF_MFMA_MIN_B overrides.
+inline int mfma_from(const pf_ctx *ctx, const pf_layer_desc &D)
+{
+    if (ctx->mfma_min_batch_forced || ctx->mfma_min_batch <= 3) return ctx->mfma_min_batch;
+    return D.d > 4096 ? 3 : ctx->mfma_min_batch;
+}
+
 // The predictor runs on the matrix cores from the same batch size on as FC1 (row length a
 // multiple of 32, and the opt-in LDS size for its 64 KB of slots + static LDS).
-inline bool pred_mfma(const pf_ctx *ctx, int K, int B)
+inline bool pred_mfma(const pf_ctx *ctx, const pf_layer_desc &D, int K, int B)
 {
-    return B >= ctx->mfma_min_batch && K % 32 == 0 && ctx->lds_budget > kLdsDefault;
+    return B >= mfma_from(ctx, D) && K % 32 == 0 && ctx->lds_budget > kLdsDefault;
 }
 
 // Predictor hidden layer.  With glue_y the layer input is formed inside the kernel as
@@ -253,7 +263,7 @@ pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const fl
     const pf_layer_desc &D = L->desc;
     if (!L->w.p1 || !L->w.p2) return fail(ctx, PF_EINVAL, "layer has no predictor weights");
     const __half *p1 = static_cast<const __half *>(L->w.p1);
-    if (pred_mfma(ctx, D.d, B) && (size_t)B * (size_t)D.d > (size_t)ctx->hidden_mfma_min_elems) {
+    if (pred_mfma(ctx, D, D.d, B) && (size_t)B * (size_t)D.d > (size_t)ctx->hidden_mfma_min_elems) {
         // a batch on the matrix cores; the glue, if any, as a kernel of its own in front
         if (glue_y) {
             pf_status s = launch_glue(ctx, x, glue_y, glue_ny, D.d, B, x_new, st);
@@ -304,7 +314,7 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
     if (s != PF_OK) return s;
     const pf_layer_desc &D = L->desc;
     const __half *p2 = static_cast<const __half *>(L->w.p2);
-    if (pred_mfma(ctx, D.r, B)) {
+    if (pred_mfma(ctx, D, D.r, B)) {
         ProfScope ps(ctx, K_PRED_OUT);
         PF_LAUNCH(ps, (pf::k_rows_mfma<64, 64, 1>), dim3(D.ffn / 64), dim3(pf::kMfmaThreads),
                   (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p2, (const float *)ctx->t, B, D.r,
@@ -412,7 +422,7 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     int up_grid = cdiv(D.ffn, pf::kUpWaves);
     if (up_grid > ctx->up_grid_cap) up_grid = ctx->up_grid_cap;
     const size_t mfma_lds = pf::up_mfma_lds_bytes(D.ffn, from_mask, gated);
-    const bool mfma = B >= ctx->mfma_min_batch && D.d % 32 == 0 && mfma_lds <= (size_t)ctx->lds_budget;
+    const bool mfma = B >= mfma_from(ctx, D) && D.d % 32 == 0 && mfma_lds <= (size_t)ctx->lds_budget;
     if (mfma) {  // the whole batch in one launch: tokens are the N columns of the tile
         // one block per CU: a block's fixed cost (mask scan, bit select, tile reduction) is about
         // 7 us, so two rounds of smaller blocks lose more than their longer chunks gain
@@ -491,14 +501,15 @@ pf_status launch_layer(pf_ctx *ctx, const pf_layer *L, const float *x, const flo
 bool fused_ok(const pf_ctx *ctx, const pf_layer *L, int B)
 {
     const pf_layer_desc &D = L->desc;
-    if (!ctx->fused || D.wtype == PF_W_INT4_G128 || B >= ctx->mfma_min_batch || B > 3 ||
+    if (!ctx->fused || D.wtype == PF_W_INT4_G128 || B >= mfma_from(ctx, D) || B > 3 ||
         pf::out_up_lds_bytes(B, D.r, D.d) + 1024 > (size_t)ctx->lds_budget)
         return false;
     if (ctx->fused > 1) return true;  // forced
     // Measured on the five benchmark shapes: the fused form wins by 8 - 20 % where the saved
     // kernel boundary weighs most (short rows, or three tokens, whose list-based kernels are
     // slow) and loses 1 - 7 % with long rows at batch 1, where FC1 and FC2 are long enough
-    // for the uneven work per segment to cost more than the boundary.
+    // for the uneven work per segment to cost more than the boundary.  (Three tokens with
+    // long rows never get here: mfma_from sends them to the matrix cores.)
     const bool gated = D.act == PF_ACT_REGLU;
     return B == 3 || D.d <= 4096 || (B == 2 && !gated);
 }
@@ -736,7 +747,10 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         }
         if (const char *v = getenv("PF_MFMA_MIN_B")) {
             int c = atoi(v);
-            if (c >= 1) ctx->mfma_min_batch = c;
+            if (c >= 1) {
+                ctx->mfma_min_batch = c;
+                ctx->mfma_min_batch_forced = true;
+            }
         }
         if (const char *v = getenv("PF_UP_GRID")) {
             int c = atoi(v);

@@ -92,7 +92,7 @@ def test_full_shape_stack_plan_matches_layer_chain(pf):
     plan.close()
 
 
-@pytest.mark.parametrize("name,B", [("opt-6.7b", 1), ("opt-6.7b", 3), ("llama2-13b-reglu", 3)])
+@pytest.mark.parametrize("name,B", [("opt-6.7b", 1), ("opt-6.7b", 3), ("opt-30b", 2)])
 def test_full_shape_stack_three_launch_form_matches_oracle(pf, oracle, name, B):
     """Three full-size layers through the recorded plan, at the shapes and batches where the
     stack's inner layers take the three-launch form (output layer + FC1 fused, FC2 over
