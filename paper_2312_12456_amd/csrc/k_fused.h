@@ -8,8 +8,9 @@
 // costs nothing: the block is there anyway, for the predictor.  No global index list is built.
 // Block g of k_out_up leaves a SEGMENT: seg_words[g] = its 64 decisions as a bit word,
 // a byte table with the positions (0 .. 63) of its active neurons, h[64 g + a][token] = the
-// FC1 output of its a-th active neuron.  FC2 deals the segments to its row slots.  One kernel boundary, one launch ramp,
-// the mask scan and the trip of the index list through memory are saved per layer.
+// FC1 output of its a-th active neuron.  FC2 deals whole segments to its waves.  One kernel
+// boundary, one launch ramp, the mask scan and the trip of the index list through memory are
+// saved per layer.
 // Work per workgroup follows the number of active neurons per segment (see seg_neuron for
 // the two ways of forming segments).  The bit words are internal; the caller-visible mask
 // format is produced by k_pred_out only.
