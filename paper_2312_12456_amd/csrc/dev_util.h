@@ -50,9 +50,19 @@ __constant__ unsigned long long *g_pf_trace = nullptr;  // [slot][4096 blocks][8
         if (threadIdx.x == 0 && g_pf_trace && blockIdx.x < 4096)                             \
             g_pf_trace[((size_t)(slot) * 4096 + blockIdx.x) * 8 + (k)] = wall_clock64();     \
     } while (0)
+// latest time any wave of the block passes this point (lane 0 of every wave)
+#define PF_TSTAMP_MAX(slot, k)                                                               \
+    do {                                                                                     \
+        if ((threadIdx.x & 63) == 0 && g_pf_trace && blockIdx.x < 4096)                      \
+            atomicMax(&g_pf_trace[((size_t)(slot) * 4096 + blockIdx.x) * 8 + (k)],           \
+                      (unsigned long long)wall_clock64());                                   \
+    } while (0)
 #else
 #define PF_TSTAMP(slot, k) \
     do {                   \
+    } while (0)
+#define PF_TSTAMP_MAX(slot, k) \
+    do {                       \
     } while (0)
 #endif
 

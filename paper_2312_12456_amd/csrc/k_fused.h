@@ -125,7 +125,10 @@ __global__ __launch_bounds__(kPredOutThreads) void k_out_up(
     }
     const int nact = __popcll(word);
     int a = wave;
-    if (a >= nact) return;  // wave-uniform; no block-level synchronisation below
+    if (a >= nact) {  // wave-uniform; no block-level synchronisation below
+        PF_TSTAMP_MAX(4, 5);
+        return;
+    }
 
     // position of set bit number `a` of the word (wave-uniform)
     auto neuron_of = [&](int rank) -> int {
@@ -176,6 +179,7 @@ __global__ __launch_bounds__(kPredOutThreads) void k_out_up(
         if (!more) break;
     }
     PF_TSTAMP(4, 4);
+    PF_TSTAMP_MAX(4, 5);
 }
 
 // FC2 over the segments k_out_up leaves (popcount(seg_words[w]) valid entries in segment w:
