@@ -140,6 +140,14 @@ inline int batch_tile(const pf_ctx *ctx, int k, int B, size_t extra)
         default: { constexpr int BT = 8; __VA_ARGS__; } break;               \
     }
 
+// The three-launch kernels exist for batch 1..3 only (fused_ok).
+#define PF_SWITCH_B3(Bt, ...)                                                \
+    switch (Bt) {                                                            \
+        case 1: { constexpr int BT = 1; __VA_ARGS__; } break;                \
+        case 2: { constexpr int BT = 2; __VA_ARGS__; } break;                \
+        default: { constexpr int BT = 3; __VA_ARGS__; } break;               \
+    }
+
 // Opt a kernel in to the full 160 KB of LDS: dynamic limit = 160 KB minus its static LDS.
 template <typename K>
 hipError_t allow_lds(K kernel)
@@ -166,8 +174,10 @@ hipError_t allow_lds_for_batch()
     if (e == hipSuccess) e = allow_lds(pf::k_up_i4<B, 1, false>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_i4<B, 0, true>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_i4<B, 1, true>);
-    if (e == hipSuccess) e = allow_lds(pf::k_out_up<B, 0>);
-    if (e == hipSuccess) e = allow_lds(pf::k_out_up<B, 1>);
+    if constexpr (B <= 3) {
+        if (e == hipSuccess) e = allow_lds(pf::k_out_up<B, 0>);
+        if (e == hipSuccess) e = allow_lds(pf::k_out_up<B, 1>);
+    }
     return e;
 }
 
@@ -532,7 +542,7 @@ pf_status launch_layer_fused(pf_ctx *ctx, const pf_layer *L, const float *x, con
     {
         ProfScope ps(ctx, K_OUT_UP);
 #define PF_OU(ACT)                                                                                \
-    PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_out_up<BT, ACT>), dim3(D.ffn / 64),                       \
+    PF_SWITCH_B3(B, PF_LAUNCH(ps, (pf::k_out_up<BT, ACT>), dim3(D.ffn / 64),                      \
                              dim3(pf::kPredOutThreads), lds, st, p2, L->w.p_bias,                 \
                              (const float *)ctx->t, w_up, w_gate, L->w.b_up, x_in, D.r, D.d,      \
                              D.ffn, pf::h_stride(B), L->thr_logit, ctx->seg_strided != 0,         \
@@ -549,7 +559,7 @@ pf_status launch_layer_fused(pf_ctx *ctx, const pf_layer *L, const float *x, con
         ProfScope ps(ctx, K_DOWN_MASK);
         const bool multi = cdiv(D.ffn / 64, 8 * P) > pf::down2m_batch(B);
 #define PF_DM(MULTI)                                                                              \
-    PF_SWITCH_B(B, PF_LAUNCH(ps, (pf::k_down2m<BT, MULTI>), dim3(tiles, P),                       \
+    PF_SWITCH_B3(B, PF_LAUNCH(ps, (pf::k_down2m<BT, MULTI>), dim3(tiles, P),                      \
                              dim3(pf::kDown2Threads), 0, st, w_down, L->w.b_down,                 \
                              (const float *)ctx->h, (const uint64_t *)ctx->mask_words2,           \
                              reinterpret_cast<const uint8_t *>(ctx->idx), ctx->ypart, D.d, D.ffn, \
