@@ -66,7 +66,8 @@ def parse_args():
 
 
 def operator_microbench(args, torch, np, pf, wl):
-    """The paper's operator test (Sec. 8.3.2 'neuron-aware operators'): one FFN layer with
+    """The paper's operator test (Sec. 8.3.3 'Neuron-aware Operator Performance', Fig.
+    "operator"): one FFN layer with
     4096 x 4096 matrices, batch 1, a uniformly random set of active rows of swept size; time
     of FC1 and FC2 against the active fraction (slope = 1 / bandwidth, intercept = latency)."""
     cfg = wl.scaled(wl.CONFIGS["opt-6.7b"], name="m0-4096x4096", layers=1, ffn=4096, r=128)
@@ -145,11 +146,11 @@ def main():
 
     # ---- workload resident in HBM ---------------------------------------------------
     t_gen = time.time()
+    ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
     if args.sort_neurons > 0:
         # hot neurons end up next to each other: have the library form its segments of 64
-        # neurons with a stride over the neuron axis (a knob it reads when a context is created)
-        os.environ.setdefault("PF_SEG_STRIDED", "1")
-    ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
+        # neurons with a stride over the neuron axis
+        ctx.set_option(pf.OPT_SEG_STRIDED, 1)
     tensors, layers = [], []
     for l in range(cfg.layers):
         t = wl.make_layer(cfg, l, args.seed, device=dev, pred_bias=not args.no_pred_bias)

@@ -174,6 +174,43 @@ pf_status pf_ctx_last_active(pf_ctx *ctx, const uint64_t **mask_words, const int
  * every other call is unaffected.  distance: 0 (off, the default) or 1. */
 pf_status pf_ctx_set_lookahead(pf_ctx *ctx, int distance);
 
+/* Dispatch and launch-shape options of a context (this library's own tuning surface; the
+ * defaults are the measured optima and every setting computes the same function).  They take
+ * effect for the calls made, and the plans created, afterwards.  value 0 restores the default
+ * rule of an option unless stated otherwise.
+ *   PF_OPT_FUSED            inner layers of a stack in three launches (see pf_stack_step):
+ *                           0 never, 1 where measured faster (default), 2 wherever it applies
+ *   PF_OPT_SEG_STRIDED      the three-launch form groups neurons g, g + ffn/64, ... into a
+ *                           segment instead of 64 neighbours (for models stored hot-first): 0 / 1
+ *   PF_OPT_MFMA_MIN_BATCH   batch size from which FC1 and the predictor run on the matrix
+ *                           cores (default rule: 4, and 3 where d > 4096); 0 = default rule
+ *   PF_OPT_HIDDEN_MFMA_MIN_ELEMS  the predictor's hidden layer joins them only above this
+ *                           B * d (default 20480; every value >= 0 is taken as given)
+ *   PF_OPT_UP_GRID          workgroups of the vector FC1 kernel (default 8 per CU; int4: 2)
+ *   PF_OPT_MFMA_GRID        workgroups of the matrix-core FC1 kernel (default one per CU)
+ *   PF_OPT_DOWN_SPLIT       row groups of FC2, 1 .. 4 (default CUs / column tiles, at most 4)
+ * Errors: PF_EINVAL for an unknown key or a value outside the stated range. */
+typedef enum {
+    PF_OPT_FUSED = 0,
+    PF_OPT_SEG_STRIDED = 1,
+    PF_OPT_MFMA_MIN_BATCH = 2,
+    PF_OPT_HIDDEN_MFMA_MIN_ELEMS = 3,
+    PF_OPT_UP_GRID = 4,
+    PF_OPT_MFMA_GRID = 5,
+    PF_OPT_DOWN_SPLIT = 6
+} pf_option;
+pf_status pf_ctx_set_option(pf_ctx *ctx, int key, int value);
+pf_status pf_ctx_get_option(const pf_ctx *ctx, int key, int *value);
+
+/* Inspection of a stack step: with a trace buffer set, pf_stack_step and the plans created
+ * afterwards store the mask words every layer used -- layer l at trace + l * (max_ffn / 64)
+ * words, bit b of word w = neuron 64 w + b whichever form the layer ran in -- for the layers
+ * l < n_layers_capacity, with one small extra launch per layer (the compute launches are the
+ * same).  trace: device buffer of n_layers_capacity * (max_ffn / 64) uint64, caller-owned;
+ * NULL switches it off.  This is how a test reads the active set of every layer of the stack
+ * (Sec. 5.1) without a host round trip between the layers. */
+pf_status pf_ctx_set_mask_trace(pf_ctx *ctx, uint64_t *trace, int n_layers_capacity);
+
 /* Glue of the synthetic FFN stack used for benchmarking (not in the paper): residual add
  * and scale-only RMS normalisation, x_next = s * (x + y) * sqrt(d) / ||x + y||_2 per token,
  * where s is a fixed +/-1 pattern over (batch row, column) that is all +1 for row 0: it keeps

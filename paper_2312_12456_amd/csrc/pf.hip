@@ -43,18 +43,20 @@ struct pf_ctx {
     int num_cu = 256;
     int up_grid_cap = 2048;
     int up_grid_cap_i4 = 512;
-    int mfma_grid = 0;              // PF_MFMA_GRID: blocks of k_up_mfma (0 = from the CU count)
+    int mfma_grid = 0;              // PF_OPT_MFMA_GRID: blocks of k_up_mfma (0 = from the CU count)
     // The hidden layer goes to the matrix cores only above this B * d: below it the vector kernel
     // with the glue fused in beats MFMA + a glue kernel of its own (measured: +1..3 % on the
     // stack at 4 x 4096 and 4 x 5120, -9 % and worse from 8 x 4096 on).
     int hidden_mfma_min_elems = 20480;
     int lds_budget = kLdsDefault;  // dynamic LDS a kernel of this context may request
-    int down_split = 0;            // PF_DOWN_SPLIT: row groups of FC2 (0 = from the CU count)
+    int down_split = 0;            // PF_OPT_DOWN_SPLIT: row groups of FC2 (0 = from the CU count)
     int mfma_min_batch = 4;        // FC1 goes to the matrix cores from this batch size on
-    bool mfma_min_batch_forced = false;  // set through PF_MFMA_MIN_B
-    int fused = 1;                 // PF_FUSED: inner layers of a stack as three launches (0 never,
+    bool mfma_min_batch_forced = false;  // set through PF_OPT_MFMA_MIN_BATCH
+    int fused = 1;                 // PF_OPT_FUSED: inner layers of a stack as three launches (0 never,
                                    // 1 where measured faster, 2 wherever possible)
-    int seg_strided = 0;           // PF_SEG_STRIDED: strided segments (models stored hot-first)
+    int seg_strided = 0;           // PF_OPT_SEG_STRIDED: strided segments (models stored hot-first)
+    uint64_t *mask_trace = nullptr;  // caller's buffer for every layer's mask words (or null)
+    int mask_trace_layers = 0;
     // scratch (device)
     float *t = nullptr;              // [max_batch][max_r] predictor hidden vector
     uint64_t *mask_words = nullptr;  // [max_ffn / 64]
@@ -251,7 +253,8 @@ pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int ny, int d
 
 // Batch size from which a layer's kernels run on the matrix cores: 4, and already 3 for rows
 // longer than 4096 (measured at batch 3: OPT-30B shape 1 001 against 925 tokens/s, LLaMA-13B
-// shape 1 439 against 1 409, but OPT-6.7B shape 2 557 against 3 042); PF_MFMA_MIN_B overrides.
+// shape 1 439 against 1 409, but OPT-6.7B shape 2 557 against 3 042); PF_OPT_MFMA_MIN_BATCH
+// overrides.
 inline int mfma_from(const pf_ctx *ctx, const pf_layer_desc &D)
 {
     if (ctx->mfma_min_batch_forced || ctx->mfma_min_batch <= 3) return ctx->mfma_min_batch;
@@ -586,6 +589,34 @@ pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int ny, int d
     return PF_OK;
 }
 
+// Copies a layer's mask words to the caller's trace buffer in the caller-visible format.
+// Segment words of the three-launch form with strided segments hold neuron p * G + g at bit p
+// of word g; they are re-ballotted here.  grid = ffn / 64, block = 64.
+__global__ __launch_bounds__(64) void k_trace_mask(const uint64_t *__restrict__ words, int nwords,
+                                                   bool strided, uint64_t *__restrict__ out)
+{
+    const int w = blockIdx.x, lane = threadIdx.x;
+    if (!strided) {
+        if (lane == 0) out[w] = words[w];
+        return;
+    }
+    const int n = w * 64 + lane;  // neuron: position n / nwords of segment n % nwords
+    const uint64_t bit = (words[n % nwords] >> (n / nwords)) & 1ull;
+    const uint64_t word = __ballot(bit != 0);
+    if (lane == 0) out[w] = word;
+}
+
+pf_status trace_mask(pf_ctx *ctx, int l, const pf_layer *L, const uint64_t *words, bool strided,
+                     hipStream_t st)
+{
+    if (!ctx->mask_trace || l >= ctx->mask_trace_layers) return PF_OK;
+    const int nwords = L->desc.ffn / 64;
+    hipLaunchKernelGGL(k_trace_mask, dim3(nwords), dim3(64), 0, st, words, nwords, strided,
+                       ctx->mask_trace + (size_t)l * (size_t)(ctx->max_ffn / 64));
+    PF_HIP(ctx, hipGetLastError());
+    return PF_OK;
+}
+
 // One decode step of the stack.  The glue between layer l-1 and layer l runs inside layer
 // l's hidden-layer kernel; only the glue after the last layer is a kernel of its own.
 // Event number `i` of the look-ahead schedule (created on demand, reused by later calls).
@@ -633,6 +664,7 @@ pf_status stack_enqueue_lookahead(pf_ctx *ctx, pf_layer *const *layers, int n_la
         ctx->last_idx = ctx->idx;
         ctx->last_count = ctx->count;
         s = launch_sparse(ctx, layers[l], cur, B, nullptr, nullptr, masks[l & 1], nullptr, &ny, st);
+        if (s == PF_OK) s = trace_mask(ctx, l, layers[l], masks[l & 1], false, st);
         if (s != PF_OK) return s;
         if (l + 1 < n_layers) {
             float *xn = ctx->xbuf[(l + 1) & 1];
@@ -669,6 +701,9 @@ pf_status stack_enqueue(pf_ctx *ctx, pf_layer *const *layers, int n_layers, cons
         else
             s = launch_layer(ctx, L, cur, gy, l == 0 ? 0 : ny, xn, B, nullptr, &ny, st);
         if (l > 0) cur = xn;
+        if (s == PF_OK)
+            s = fused ? trace_mask(ctx, l, L, ctx->mask_words2, ctx->seg_strided != 0, st)
+                      : trace_mask(ctx, l, L, ctx->mask_words, false, st);
         if (s != PF_OK) return s;
     }
     return launch_glue(ctx, cur, ctx->ypart, ny, layers[0]->desc.d, B, x_out, st);
@@ -744,28 +779,6 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         ctx->up_grid_cap = 8 * ctx->num_cu;
         ctx->up_grid_cap_i4 = 2 * ctx->num_cu;
         ctx->mfma_grid = 0;  // 0: from the CU count
-        if (const char *v = getenv("PF_HIDDEN_MFMA_MIN_ELEMS")) ctx->hidden_mfma_min_elems = atoi(v);
-        if (const char *v = getenv("PF_FUSED")) ctx->fused = atoi(v);
-        if (const char *v = getenv("PF_SEG_STRIDED")) ctx->seg_strided = atoi(v) != 0;
-        if (const char *v = getenv("PF_MFMA_GRID")) {
-            int c = atoi(v);
-            if (c >= 1 && c <= 65535) ctx->mfma_grid = c;
-        }
-        if (const char *v = getenv("PF_DOWN_SPLIT")) {
-            int c = atoi(v);
-            if (c >= 1 && c <= pf::kDown2MaxSplit) ctx->down_split = c;
-        }
-        if (const char *v = getenv("PF_MFMA_MIN_B")) {
-            int c = atoi(v);
-            if (c >= 1) {
-                ctx->mfma_min_batch = c;
-                ctx->mfma_min_batch_forced = true;
-            }
-        }
-        if (const char *v = getenv("PF_UP_GRID")) {
-            int c = atoi(v);
-            if (c >= 1 && c <= 65535) ctx->up_grid_cap = ctx->up_grid_cap_i4 = c;
-        }
         // larger staged batches need the opt-in LDS size; without it batches are tiled smaller
         if (prop.sharedMemPerBlock >= (size_t)kLdsMax ||
             prop.maxSharedMemoryPerMultiProcessor >= (size_t)kLdsMax) {
@@ -989,6 +1002,71 @@ pf_status pf_ctx_set_lookahead(pf_ctx *ctx, int distance)
     if (!ctx) return PF_EINVAL;
     if (distance != 0 && distance != 1) return fail(ctx, PF_EINVAL, "look-ahead distance %d: 0 or 1", distance);
     ctx->lookahead = distance;
+    return PF_OK;
+}
+
+pf_status pf_ctx_set_option(pf_ctx *ctx, int key, int value)
+{
+    if (!ctx) return PF_EINVAL;
+    switch (key) {
+        case PF_OPT_FUSED:
+            if (value < 0 || value > 2) break;
+            ctx->fused = value;
+            return PF_OK;
+        case PF_OPT_SEG_STRIDED:
+            if (value < 0 || value > 1) break;
+            ctx->seg_strided = value;
+            return PF_OK;
+        case PF_OPT_MFMA_MIN_BATCH:
+            if (value < 0) break;
+            ctx->mfma_min_batch = value > 0 ? value : 4;
+            ctx->mfma_min_batch_forced = value > 0;
+            return PF_OK;
+        case PF_OPT_HIDDEN_MFMA_MIN_ELEMS:
+            if (value < 0) break;
+            ctx->hidden_mfma_min_elems = value;
+            return PF_OK;
+        case PF_OPT_UP_GRID:
+            if (value < 0 || value > 65535) break;
+            ctx->up_grid_cap = value > 0 ? value : 8 * ctx->num_cu;
+            ctx->up_grid_cap_i4 = value > 0 ? value : 2 * ctx->num_cu;
+            return PF_OK;
+        case PF_OPT_MFMA_GRID:
+            if (value < 0 || value > 65535) break;
+            ctx->mfma_grid = value;
+            return PF_OK;
+        case PF_OPT_DOWN_SPLIT:
+            if (value < 0 || value > pf::kDown2MaxSplit) break;
+            ctx->down_split = value;
+            return PF_OK;
+        default:
+            return fail(ctx, PF_EINVAL, "unknown option %d", key);
+    }
+    return fail(ctx, PF_EINVAL, "option %d: value %d out of range", key, value);
+}
+
+pf_status pf_ctx_get_option(const pf_ctx *ctx, int key, int *value)
+{
+    if (!ctx || !value) return PF_EINVAL;
+    switch (key) {
+        case PF_OPT_FUSED: *value = ctx->fused; break;
+        case PF_OPT_SEG_STRIDED: *value = ctx->seg_strided; break;
+        case PF_OPT_MFMA_MIN_BATCH: *value = ctx->mfma_min_batch_forced ? ctx->mfma_min_batch : 0; break;
+        case PF_OPT_HIDDEN_MFMA_MIN_ELEMS: *value = ctx->hidden_mfma_min_elems; break;
+        case PF_OPT_UP_GRID: *value = ctx->up_grid_cap; break;
+        case PF_OPT_MFMA_GRID: *value = ctx->mfma_grid; break;
+        case PF_OPT_DOWN_SPLIT: *value = ctx->down_split; break;
+        default: return PF_EINVAL;
+    }
+    return PF_OK;
+}
+
+pf_status pf_ctx_set_mask_trace(pf_ctx *ctx, uint64_t *trace, int n_layers_capacity)
+{
+    if (!ctx) return PF_EINVAL;
+    if (trace && n_layers_capacity < 1) return fail(ctx, PF_EINVAL, "trace buffer without capacity");
+    ctx->mask_trace = trace;
+    ctx->mask_trace_layers = trace ? n_layers_capacity : 0;
     return PF_OK;
 }
 

@@ -22,8 +22,13 @@ EXPORTS = [
     "pf_compact", "pf_sparse_ffn", "pf_layer_step", "pf_ctx_last_active", "pf_stack_glue",
     "pf_stack_step", "pf_plan_create", "pf_plan_run", "pf_plan_destroy", "pf_strerror",
     "pf_last_error", "pf_version", "pf_profile_begin", "pf_profile_end", "pf_dense_ffn",
-    "pf_layer_step_auto", "pf_count_activations", "pf_ctx_set_lookahead",
+    "pf_layer_step_auto", "pf_count_activations", "pf_ctx_set_lookahead", "pf_ctx_set_option",
+    "pf_ctx_get_option", "pf_ctx_set_mask_trace",
 ]
+
+# pf_option keys
+(OPT_FUSED, OPT_SEG_STRIDED, OPT_MFMA_MIN_BATCH, OPT_HIDDEN_MFMA_MIN_ELEMS, OPT_UP_GRID,
+ OPT_MFMA_GRID, OPT_DOWN_SPLIT) = range(7)
 
 
 class PfError(RuntimeError):
@@ -76,6 +81,9 @@ def lib():
         L.pf_layer_step_auto.argtypes = [P, P, P, I, ctypes.c_float, ctypes.c_float, P, P]
         L.pf_count_activations.argtypes = [P, P, P, P]
         L.pf_ctx_set_lookahead.argtypes = [P, I]
+        L.pf_ctx_set_option.argtypes = [P, I, I]
+        L.pf_ctx_get_option.argtypes = [P, I, ctypes.POINTER(I)]
+        L.pf_ctx_set_mask_trace.argtypes = [P, P, I]
         L.pf_stack_glue.argtypes = [P, P, P, I, I, P, P]
         L.pf_stack_step.argtypes = [P, PP, I, P, I, P, P]
         L.pf_plan_create.argtypes = [P, PP, I, P, I, P, P, PP]
@@ -122,6 +130,8 @@ class Context:
         if st != PF_OK:
             raise PfError(st, lib().pf_strerror(st).decode())
         self.device = device
+        self.max_ffn = max_ffn
+        self._trace = None
 
     def check(self, st):
         if st != PF_OK:
@@ -155,7 +165,8 @@ class Context:
     def sparse_ffn(self, layer, x, idx, count, y, stream=None):
         B = x.shape[0]
         self.check(lib().pf_sparse_ffn(self._h, layer._h, _dev_ptr(x, torch.float32, B * layer.d), B,
-                                       _dev_ptr(idx, torch.int32), _dev_ptr(count, torch.int32, 1),
+                                       _dev_ptr(idx, torch.int32, layer.ffn),
+                                       _dev_ptr(count, torch.int32, 1),
                                        _dev_ptr(y, torch.float32, B * layer.d), _stream_ptr(stream)))
 
     def layer_step(self, layer, x, y, stream=None):
@@ -181,6 +192,23 @@ class Context:
 
     def set_lookahead(self, distance):
         self.check(lib().pf_ctx_set_lookahead(self._h, int(distance)))
+
+    def set_option(self, key, value):
+        self.check(lib().pf_ctx_set_option(self._h, int(key), int(value)))
+
+    def get_option(self, key):
+        v = ctypes.c_int(0)
+        self.check(lib().pf_ctx_get_option(self._h, int(key), ctypes.byref(v)))
+        return v.value
+
+    def set_mask_trace(self, trace, n_layers=0):
+        """trace: int64 device tensor of n_layers * (max_ffn / 64) words, or None to switch off."""
+        if trace is None:
+            self.check(lib().pf_ctx_set_mask_trace(self._h, None, 0))
+        else:
+            self.check(lib().pf_ctx_set_mask_trace(
+                self._h, _dev_ptr(trace, torch.int64, n_layers * (self.max_ffn // 64)), n_layers))
+        self._trace = trace  # keeps the buffer alive while the library may write to it
 
     def last_active(self):
         """(mask_words, idx, count) device addresses left by the last layer_step."""

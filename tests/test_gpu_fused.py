@@ -1,14 +1,17 @@
 """GPU parity of the three-launch form of the layer step used inside a stack (predictor output
 layer and FC1 in one kernel per 64-neuron segment, FC2 over the segments; PowerInfer Sec. 5.1 +
-5.4): against the fp64 oracle's stack, and against the four-launch form of the same library,
-for both ways of forming segments, batch 1..3, both activations, ragged row lengths, and
-densities from a few to most neurons of a segment (every round of the FC2 kernel)."""
+5.4): against the fp64 oracle -- every layer's active set bit-exact outside the score band,
+and the stack output against the oracle's stack run on those sets -- and against the
+four-launch form of the same library, for both ways of forming segments, batch 1..3, both
+activations, ragged row lengths, and densities from a few to most neurons of a segment (every
+round of the FC2 kernel)."""
 import numpy as np
 import pytest
 import torch
 
 from paper_2312_12456_amd import workload as wl
-from tests.util import SCORE_BAND, check_output, oracle_layer, small_cfg
+from tests.util import (MaskTrace, check_output, oracle_chain_on_device_sets, oracle_layer,
+                        small_cfg)
 
 pytestmark = pytest.mark.gpu
 
@@ -21,23 +24,11 @@ def pf():
     return pfmod
 
 
-def _ctx(pf, monkeypatch, cfg, B, fused, strided):
-    # the knobs are read when a context is created
-    monkeypatch.setenv("PF_FUSED", str(fused))
-    monkeypatch.setenv("PF_SEG_STRIDED", str(strided))
-    return pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
-
-
-def _oracle_stack(oracle, Os, x0, threshold):
-    """Oracle stack output and whether any predictor score of any layer sits in the band
-    around the threshold (then the active sets may legitimately differ)."""
-    xo = x0
-    in_band = False
-    for O in Os:
-        sc = O.predict(xo)["scores"]
-        in_band = in_band or bool((np.abs(sc - threshold) < SCORE_BAND).any())
-        xo = oracle.stack_glue(xo, O.layer_step(xo))
-    return xo, in_band
+def _ctx(pf, cfg, B, fused, strided):
+    ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
+    ctx.set_option(pf.OPT_FUSED, fused)
+    ctx.set_option(pf.OPT_SEG_STRIDED, strided)
+    return ctx
 
 
 CASES = [
@@ -53,20 +44,34 @@ CASES = [
 @pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
 @pytest.mark.parametrize("B", [1, 2, 3])
 @pytest.mark.parametrize("case", range(len(CASES)))
-def test_fused_stack_matches_oracle_and_list_form(pf, oracle, monkeypatch, case, B, act, strided):
+def test_fused_stack_matches_oracle_and_list_form(pf, oracle, case, B, act, strided):
     d, ffn, r, rate = CASES[case]
     cfg = small_cfg(d=d, ffn=ffn, r=r, act=act, rate=rate, layers=4)
     seed = 100 + 7 * case + B
     lays = [wl.make_layer(cfg, l, seed, device="cuda") for l in range(cfg.layers)]
+    Os = [oracle_layer(cfg, wl.to_host(t)) for t in lays]
     x0 = wl.make_inputs(cfg, 0, seed=seed, batch=B, device="cuda")
-    outs = {}
+    outs, compared = {}, 0
     for fused in (0, 2):
-        ctx = _ctx(pf, monkeypatch, cfg, B, fused, strided)
+        ctx = _ctx(pf, cfg, B, fused, strided)
+        assert ctx.get_option(pf.OPT_FUSED) == fused
         Ls = [pf.Layer.from_workload(ctx, cfg, t) for t in lays]
+        trace = MaskTrace(ctx, cfg.layers, cfg.ffn)
         out = torch.full_like(x0, float("nan"))
+        ctx.profile_begin()
         ctx.stack_step(Ls, x0, out)
+        stats = ctx.profile_end()
         torch.cuda.synchronize()
+        # the form asked for is the form that ran
+        assert stats["k_out_up"][0] == (cfg.layers - 1 if fused else 0), stats
+        assert stats["k_down_mask"][0] == (cfg.layers - 1 if fused else 0), stats
         outs[fused] = out.cpu().numpy()
+        # against the oracle, always: the oracle's stack driven by the sets this run used, each
+        # set bit-exact outside the score band
+        ref, n_cmp, _ = oracle_chain_on_device_sets(oracle, Os, x0.cpu().numpy(), trace.masks(),
+                                                    cfg.threshold, "fused=%d" % fused)
+        check_output(outs[fused], ref, "stack (fused=%d) case %d B %d" % (fused, case, B))
+        compared += n_cmp
         if fused:
             # the last layer keeps the caller-visible list: ascending, no duplicates, in range
             _, iptr, cptr = ctx.last_active()
@@ -76,30 +81,28 @@ def test_fused_stack_matches_oracle_and_list_form(pf, oracle, monkeypatch, case,
             pf.copy_from_device_address(cnt, cptr)
             n = int(cnt.item())
             lst = idx.cpu().numpy()[:n]
-            assert 0 < n <= cfg.ffn and (np.diff(lst) > 0).all() and lst[0] >= 0 and lst[-1] < cfg.ffn
-            # replayed plan == eager, bit for bit
+            assert np.array_equal(lst, np.flatnonzero(trace.masks()[-1]))
+            # replayed plan == eager, bit for bit (the plan also fills the trace)
+            first = [m.copy() for m in trace.masks()]
             out_plan = torch.zeros_like(x0)
             plan = pf.Plan(ctx, Ls, x0, out_plan)
             for _ in range(2):
                 out_plan.fill_(float("nan"))
+                trace.buf.fill_(-1)
                 plan.run()
                 torch.cuda.synchronize()
                 assert torch.equal(out_plan, out)
+                assert all(np.array_equal(a, b) for a, b in zip(trace.masks(), first))
             plan.close()
+        ctx.set_mask_trace(None)
+    assert compared == 2 * cfg.layers
     # same predictor arithmetic, same FC1 arithmetic, another order of FC2's sum
     np.testing.assert_allclose(outs[2], outs[0], atol=2e-4, rtol=0)
-    Os = [oracle_layer(cfg, wl.to_host(t)) for t in lays]
-    ref, in_band = _oracle_stack(oracle, Os, x0.cpu().numpy(), cfg.threshold)
-    if not in_band:
-        check_output(outs[2], ref, "fused stack case %d B %d" % (case, B))
-        check_output(outs[0], ref, "list stack case %d B %d" % (case, B))
 
 
-def test_fused_form_is_what_runs_by_default(pf, monkeypatch):
+def test_fused_form_is_what_runs_by_default(pf):
     """At the headline shape class (d <= 4096, batch 1) the inner layers of a stack take the
     three-launch form: the per-kernel profile of an eager step shows its kernels."""
-    monkeypatch.delenv("PF_FUSED", raising=False)
-    monkeypatch.delenv("PF_SEG_STRIDED", raising=False)
     cfg = small_cfg(d=1024, ffn=2048, r=128, layers=3)
     ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=1)
     lays = [wl.make_layer(cfg, l, 5, device="cuda") for l in range(cfg.layers)]

@@ -54,3 +54,38 @@ def check_active_set(dev_mask, ref_scores, threshold, what=""):
     assert not bad.any(), "%s: %d active-set mismatches outside the band, first %s" % (
         what, int(bad.sum()), np.flatnonzero(bad)[:8])
     return int((~comparable).sum())
+
+
+def words_to_mask(words, ffn):
+    """uint64 / int64 mask words (numpy) -> bool [ffn]; bit b of word w = neuron 64 w + b."""
+    w = np.ascontiguousarray(np.asarray(words)).view(np.uint8)
+    return np.unpackbits(w, bitorder="little")[:ffn].astype(bool)
+
+
+class MaskTrace:
+    """Device buffer the library fills with every layer's mask words during a stack step."""
+
+    def __init__(self, ctx, n_layers, ffn):
+        import torch
+        self.n_layers, self.ffn, self.stride = n_layers, ffn, ctx.max_ffn // 64
+        self.buf = torch.full((n_layers * self.stride,), -1, dtype=torch.int64, device="cuda")
+        ctx.set_mask_trace(self.buf, n_layers)
+
+    def masks(self):
+        host = self.buf.cpu().numpy().reshape(self.n_layers, self.stride)
+        return [words_to_mask(host[l, :self.ffn // 64], self.ffn) for l in range(self.n_layers)]
+
+
+def oracle_chain_on_device_sets(oracle_mod, Os, x0, masks, threshold, what=""):
+    """The oracle's stack driven by the active sets the device used, layer by layer: the set of
+    layer l must equal the oracle's prediction on the oracle's own input to that layer outside
+    the score band; the oracle then runs its masked FFN on exactly that set, so a flip inside
+    the band never leaks into the output comparison.  -> (oracle stack output, number of
+    layers compared, number of (token, neuron) scores that lay inside the band)."""
+    xo = np.asarray(x0, dtype=np.float32)
+    in_band = 0
+    for l, (O, m) in enumerate(zip(Os, masks)):
+        sc = O.predict(xo)["scores"]
+        in_band += check_active_set(m, sc, threshold, "%s layer %d" % (what, l))
+        xo = oracle_mod.stack_glue(xo, O.masked_ffn(xo, m))
+    return xo, len(masks), in_band
