@@ -726,6 +726,62 @@ pf_status check_stack(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const 
     return PF_OK;
 }
 
+// Launch-shape defaults that follow from the device (CU count, LDS opt-in); shared by every
+// way a context comes into being.  The device must be current.
+hipError_t init_device_limits(pf_ctx *ctx, int device)
+{
+    hipDeviceProp_t prop;
+    hipError_t e = hipGetDeviceProperties(&prop, device);
+    if (e != hipSuccess) return e;
+    if (prop.multiProcessorCount > 0) ctx->num_cu = prop.multiProcessorCount;
+    ctx->up_grid_cap = 8 * ctx->num_cu;
+    ctx->up_grid_cap_i4 = 2 * ctx->num_cu;
+    ctx->mfma_grid = 0;  // 0: from the CU count
+    // larger staged batches need the opt-in LDS size; without it batches are tiled smaller
+    if (prop.sharedMemPerBlock >= (size_t)kLdsMax ||
+        prop.maxSharedMemoryPerMultiProcessor >= (size_t)kLdsMax) {
+        if (allow_lds_all() == hipSuccess)
+            ctx->lds_budget = kLdsMax - 4096;  // room for the kernels' small static LDS
+        else
+            (void)hipGetLastError();
+    }
+    return hipSuccess;
+}
+
+// Descriptor and weight pointers of a layer against the limits of the context that will run it.
+pf_status check_layer(pf_ctx *ctx, const pf_layer_desc *desc, const pf_layer_weights *w)
+{
+    if (!desc || !w) return fail(ctx, PF_EINVAL, "null descriptor or weights");
+    if (desc->d < 1 || desc->ffn < 1 || desc->r < 1)
+        return fail(ctx, PF_EINVAL, "non-positive size");
+    if (!(desc->threshold > 0.f && desc->threshold < 1.f))
+        return fail(ctx, PF_EINVAL, "threshold %g outside (0,1)", (double)desc->threshold);
+    if (desc->act != PF_ACT_RELU && desc->act != PF_ACT_REGLU)
+        return fail(ctx, PF_EUNSUPPORTED, "activation %d", desc->act);
+    if (desc->wtype != PF_W_FP16 && desc->wtype != PF_W_INT4_G128)
+        return fail(ctx, PF_EUNSUPPORTED, "weight type %d", desc->wtype);
+    if (desc->ffn % 64 != 0) return fail(ctx, PF_ESHAPE, "ffn %d is not a multiple of 64", desc->ffn);
+    if (desc->d % 8 != 0) return fail(ctx, PF_ESHAPE, "d %d is not a multiple of 8", desc->d);
+    if (desc->r % 8 != 0) return fail(ctx, PF_ESHAPE, "r %d is not a multiple of 8", desc->r);
+    if (desc->wtype == PF_W_INT4_G128 && desc->d % 128 != 0)
+        return fail(ctx, PF_ESHAPE, "int4 needs d %% 128 == 0, got %d", desc->d);
+    if (desc->d > ctx->max_d || desc->ffn > ctx->max_ffn || desc->r > ctx->max_r)
+        return fail(ctx, PF_ESHAPE, "layer (d=%d, ffn=%d, r=%d) exceeds context (%d, %d, %d)",
+                    desc->d, desc->ffn, desc->r, ctx->max_d, ctx->max_ffn, ctx->max_r);
+    // kernels address a matrix through a 32-bit buffer descriptor
+    if ((uint64_t)desc->ffn * desc->d * 2 >= (1ull << 32) || (uint64_t)desc->ffn * desc->r * 2 >= (1ull << 32))
+        return fail(ctx, PF_ESHAPE, "a weight matrix of 4 GiB or more is not supported");
+    if (!w->w_up || !w->w_down) return fail(ctx, PF_EINVAL, "w_up / w_down is null");
+    if (desc->act == PF_ACT_REGLU && !w->w_gate) return fail(ctx, PF_EINVAL, "gated layer without w_gate");
+    if ((w->p1 == nullptr) != (w->p2 == nullptr))
+        return fail(ctx, PF_EINVAL, "p1 and p2 must both be given or both be null");
+    if (desc->wtype == PF_W_INT4_G128) {
+        if (!w->s_up || !w->s_down || (desc->act == PF_ACT_REGLU && !w->s_gate))
+            return fail(ctx, PF_EINVAL, "int4 layer without scales");
+    }
+    return PF_OK;
+}
+
 __global__ void k_iota(int32_t *idx, int n, int32_t *count)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -772,21 +828,8 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
     do {
         hipError_t e = hipSetDevice(device);
         if (e != hipSuccess) { st = PF_EHIP; break; }
-        hipDeviceProp_t prop;
-        e = hipGetDeviceProperties(&prop, device);
+        e = init_device_limits(ctx, device);
         if (e != hipSuccess) { st = PF_EHIP; break; }
-        if (prop.multiProcessorCount > 0) ctx->num_cu = prop.multiProcessorCount;
-        ctx->up_grid_cap = 8 * ctx->num_cu;
-        ctx->up_grid_cap_i4 = 2 * ctx->num_cu;
-        ctx->mfma_grid = 0;  // 0: from the CU count
-        // larger staged batches need the opt-in LDS size; without it batches are tiled smaller
-        if (prop.sharedMemPerBlock >= (size_t)kLdsMax ||
-            prop.maxSharedMemoryPerMultiProcessor >= (size_t)kLdsMax) {
-            if (allow_lds_all() == hipSuccess)
-                ctx->lds_budget = kLdsMax - 4096;  // room for the kernels' small static LDS
-            else
-                (void)hipGetLastError();
-        }
         if ((size_t)kpad_i4(max_d) * sizeof(float) + pf::up_mask_lds_bytes(max_ffn) + 1024 >
             (size_t)ctx->lds_budget) {
             st = PF_ESHAPE;
@@ -854,34 +897,8 @@ pf_status pf_layer_create(pf_ctx *ctx, const pf_layer_desc *desc, const pf_layer
     if (!ctx) return PF_EINVAL;
     if (!out) return fail(ctx, PF_EINVAL, "out is null");
     *out = nullptr;
-    if (!desc || !w) return fail(ctx, PF_EINVAL, "null descriptor or weights");
-    if (desc->d < 1 || desc->ffn < 1 || desc->r < 1)
-        return fail(ctx, PF_EINVAL, "non-positive size");
-    if (!(desc->threshold > 0.f && desc->threshold < 1.f))
-        return fail(ctx, PF_EINVAL, "threshold %g outside (0,1)", (double)desc->threshold);
-    if (desc->act != PF_ACT_RELU && desc->act != PF_ACT_REGLU)
-        return fail(ctx, PF_EUNSUPPORTED, "activation %d", desc->act);
-    if (desc->wtype != PF_W_FP16 && desc->wtype != PF_W_INT4_G128)
-        return fail(ctx, PF_EUNSUPPORTED, "weight type %d", desc->wtype);
-    if (desc->ffn % 64 != 0) return fail(ctx, PF_ESHAPE, "ffn %d is not a multiple of 64", desc->ffn);
-    if (desc->d % 8 != 0) return fail(ctx, PF_ESHAPE, "d %d is not a multiple of 8", desc->d);
-    if (desc->r % 8 != 0) return fail(ctx, PF_ESHAPE, "r %d is not a multiple of 8", desc->r);
-    if (desc->wtype == PF_W_INT4_G128 && desc->d % 128 != 0)
-        return fail(ctx, PF_ESHAPE, "int4 needs d %% 128 == 0, got %d", desc->d);
-    if (desc->d > ctx->max_d || desc->ffn > ctx->max_ffn || desc->r > ctx->max_r)
-        return fail(ctx, PF_ESHAPE, "layer (d=%d, ffn=%d, r=%d) exceeds context (%d, %d, %d)",
-                    desc->d, desc->ffn, desc->r, ctx->max_d, ctx->max_ffn, ctx->max_r);
-    // kernels address a matrix through a 32-bit buffer descriptor
-    if ((uint64_t)desc->ffn * desc->d * 2 >= (1ull << 32) || (uint64_t)desc->ffn * desc->r * 2 >= (1ull << 32))
-        return fail(ctx, PF_ESHAPE, "a weight matrix of 4 GiB or more is not supported");
-    if (!w->w_up || !w->w_down) return fail(ctx, PF_EINVAL, "w_up / w_down is null");
-    if (desc->act == PF_ACT_REGLU && !w->w_gate) return fail(ctx, PF_EINVAL, "gated layer without w_gate");
-    if ((w->p1 == nullptr) != (w->p2 == nullptr))
-        return fail(ctx, PF_EINVAL, "p1 and p2 must both be given or both be null");
-    if (desc->wtype == PF_W_INT4_G128) {
-        if (!w->s_up || !w->s_down || (desc->act == PF_ACT_REGLU && !w->s_gate))
-            return fail(ctx, PF_EINVAL, "int4 layer without scales");
-    }
+    const pf_status chk = check_layer(ctx, desc, w);
+    if (chk != PF_OK) return chk;
     pf_layer *L = new (std::nothrow) pf_layer();
     if (!L) return fail(ctx, PF_ENOMEM, "host allocation failed");
     L->ctx = ctx;
