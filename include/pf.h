@@ -38,7 +38,8 @@ typedef enum {
     PF_ESHAPE = 2,       /* ffn % 64, d % 8, r % 8, (int4) d % 128, layer larger than ctx */
     PF_ENOMEM = 3,       /* device or host allocation failed                             */
     PF_EHIP = 4,         /* a HIP call failed; pf_last_error has its text                */
-    PF_EUNSUPPORTED = 5  /* activation / weight type combination not built               */
+    PF_EUNSUPPORTED = 5, /* activation / weight type combination not built               */
+    PF_ELIMIT = 6        /* pf_layer_step_noalloc: a size beyond its fixed maxima        */
 } pf_status;
 
 typedef enum {
@@ -133,6 +134,23 @@ pf_status pf_sparse_ffn(pf_ctx *ctx, const pf_layer *layer, const float *x, int 
  * host involvement (Sec. 4.2 without the CPU half).  x [B][d] -> y [B][d]. */
 pf_status pf_layer_step(pf_ctx *ctx, const pf_layer *layer, const float *x, int B, float *y,
                         void *stream);
+
+/* pf_layer_step for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The same kernels and launches as
+ * pf_layer_step, but no context: the scratch (hidden vector, mask words, index list, count,
+ * FC1 outputs, FC2 partial sums) is a fixed array in the library's device image, about 1.2 MB
+ * that every GPU the library runs on holds until the process ends.  The call allocates and
+ * frees nothing, on the device or through any library.  It runs on the calling thread's
+ * current device; desc / w as for pf_layer_create (weights are only read during the call's
+ * kernels), x [B][d] -> y [B][d], asynchronous on `stream`.
+ * Limits: d <= 8192, ffn <= 32768, r <= 2048, B <= 4; beyond them PF_ELIMIT, before anything is
+ * launched.  Other argument errors as for pf_layer_create / pf_layer_step (status only: there
+ * is no context to hold a message).
+ * All calls on one GPU share that GPU's array, which keeps the previous call's contents: every
+ * piece is rewritten before it is read, so nothing needs clearing, but two calls that overlap
+ * on one GPU (different streams or threads) race -- serialise them. */
+pf_status pf_layer_step_noalloc(const pf_layer_desc *desc, const pf_layer_weights *w, const float *x,
+                                int B, float *y, void *stream);
 
 /* Dense FFN of the layer: every neuron is computed and the predictor is not used
  * (Sec. 8.2: dense computation when the joint activation of a long prompt or a large batch

@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -118,6 +119,7 @@ pf_status fail(pf_ctx *ctx, pf_status s, const char *fmt, ...)
     } while (0)
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+inline float logit_of(float tau) { return (float)std::log((double)tau / (1.0 - (double)tau)); }
 inline int kpad_of(int k) { return cdiv(k, pf::kChunk) * pf::kChunk; }
 
 // Largest batch tile whose staged activations ([tile][kpad] fp32) plus `extra` bytes fit LDS.
@@ -800,6 +802,63 @@ __global__ void k_count_activations(const int32_t *__restrict__ idx, const int32
     }
 }
 
+
+// ---- layer step for callers that cannot allocate -----------------------------------------
+// Scratch of pf_layer_step_noalloc: a fixed device array instead of a context's allocations.
+// Pieces (each a multiple of 256 bytes): hidden vector t, mask words, index list, count, FC1
+// outputs h, FC2 partial sums.
+constexpr int kNaMaxD = 8192, kNaMaxFfn = 32768, kNaMaxR = 2048, kNaMaxBatch = 4;
+constexpr size_t kNaOffT = 0;
+constexpr size_t kNaOffMask = kNaOffT + (size_t)kNaMaxBatch * kNaMaxR * sizeof(float);
+constexpr size_t kNaOffIdx = kNaOffMask + (size_t)(kNaMaxFfn / 64) * sizeof(uint64_t);
+constexpr size_t kNaOffCount = kNaOffIdx + (size_t)kNaMaxFfn * sizeof(int32_t);
+constexpr size_t kNaOffH = kNaOffCount + 256;
+constexpr size_t kNaOffYpart = kNaOffH + (size_t)pf::h_stride(kNaMaxBatch) * kNaMaxFfn * sizeof(float);
+constexpr size_t kNaScratchBytes =
+    kNaOffYpart + (size_t)pf::kDown2MaxSplit * kNaMaxBatch * kNaMaxD * sizeof(float);
+static_assert(kNaOffMask % 256 == 0 && kNaOffIdx % 256 == 0 && kNaOffCount % 256 == 0 &&
+                  kNaOffH % 256 == 0 && kNaOffYpart % 256 == 0,
+              "scratch pieces keep the array's alignment");
+
+static __device__ __align__(256) unsigned char scratch[kNaScratchBytes];  // about 1.2 MB per GPU
+
+constexpr int kNaMaxDevices = 64;
+struct NoAllocState {
+    bool ready = false;
+    pf_ctx ctx;  // a context whose scratch pointers lie inside this device's copy of `scratch`
+};
+NoAllocState g_noalloc[kNaMaxDevices];
+std::mutex g_noalloc_mutex;
+
+// First call on a device: the device address of its copy of `scratch` (the array's name is
+// only a host-side handle) and the launch limits of the device.  Nothing is allocated.
+pf_status noalloc_state(int device, pf_ctx **out)
+{
+    std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+    NoAllocState &S = g_noalloc[device];
+    if (!S.ready) {
+        unsigned char *ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return PF_EHIP;
+        pf_ctx &c = S.ctx;
+        c.device = device;
+        c.max_d = kNaMaxD;
+        c.max_ffn = kNaMaxFfn;
+        c.max_r = kNaMaxR;
+        c.max_batch = kNaMaxBatch;
+        if (init_device_limits(&c, device) != hipSuccess) return PF_EHIP;
+        c.t = reinterpret_cast<float *>(ptr + kNaOffT);
+        c.mask_words = reinterpret_cast<uint64_t *>(ptr + kNaOffMask);
+        c.idx = reinterpret_cast<int32_t *>(ptr + kNaOffIdx);
+        c.count = reinterpret_cast<int32_t *>(ptr + kNaOffCount);
+        c.h = reinterpret_cast<float *>(ptr + kNaOffH);
+        c.ypart = reinterpret_cast<float *>(ptr + kNaOffYpart);
+        S.ready = true;
+    }
+    *out = &S.ctx;
+    return PF_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -904,8 +963,7 @@ pf_status pf_layer_create(pf_ctx *ctx, const pf_layer_desc *desc, const pf_layer
     L->ctx = ctx;
     L->desc = *desc;
     L->w = *w;
-    const double tau = (double)desc->threshold;
-    L->thr_logit = (float)std::log(tau / (1.0 - tau));
+    L->thr_logit = logit_of(desc->threshold);
     *out = L;
     return PF_OK;
 }
@@ -957,6 +1015,31 @@ pf_status pf_layer_step(pf_ctx *ctx, const pf_layer *layer, const float *x, int 
     if (!layer->w.p1) return fail(ctx, PF_EINVAL, "layer has no predictor weights");
     return launch_layer(ctx, layer, x, nullptr, 0, nullptr, B, y, nullptr,
                         static_cast<hipStream_t>(stream));
+}
+
+pf_status pf_layer_step_noalloc(const pf_layer_desc *desc, const pf_layer_weights *w, const float *x,
+                                int B, float *y, void *stream)
+{
+    if (!desc || !w || !x || !y) return PF_EINVAL;
+    if (desc->d > kNaMaxD || desc->ffn > kNaMaxFfn || desc->r > kNaMaxR || B > kNaMaxBatch)
+        return PF_ELIMIT;
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return PF_EHIP;
+    if (device < 0 || device >= kNaMaxDevices) return PF_ELIMIT;
+    pf_ctx *ctx = nullptr;
+    pf_status s = noalloc_state(device, &ctx);
+    if (s != PF_OK) return s;
+    s = check_layer(ctx, desc, w);
+    if (s != PF_OK) return s;
+    if (!w->p1) return PF_EINVAL;
+    pf_layer L;  // on the stack: the kernels take the weight pointers, not the handle
+    L.ctx = ctx;
+    L.desc = *desc;
+    L.w = *w;
+    L.thr_logit = logit_of(desc->threshold);
+    s = check_batch(ctx, &L, x, B);
+    if (s != PF_OK) return s;
+    return launch_layer(ctx, &L, x, nullptr, 0, nullptr, B, y, nullptr, static_cast<hipStream_t>(stream));
 }
 
 pf_status pf_dense_ffn(pf_ctx *ctx, const pf_layer *layer, const float *x, int B, float *y,
@@ -1199,6 +1282,7 @@ const char *pf_strerror(pf_status s)
         case PF_ENOMEM: return "out of memory";
         case PF_EHIP: return "HIP runtime error";
         case PF_EUNSUPPORTED: return "not supported";
+        case PF_ELIMIT: return "size beyond the fixed limits of the no-allocation entry point";
     }
     return "unknown status";
 }

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # PF_LIB_PATH selects another build of the same library (kernel tuning experiments)
 LIB_PATH = os.environ.get("PF_LIB_PATH") or os.path.join(_HERE, "libpf.so")
 
-PF_OK, PF_EINVAL, PF_ESHAPE, PF_ENOMEM, PF_EHIP, PF_EUNSUPPORTED = range(6)
+PF_OK, PF_EINVAL, PF_ESHAPE, PF_ENOMEM, PF_EHIP, PF_EUNSUPPORTED, PF_ELIMIT = range(7)
 ACT_RELU, ACT_REGLU = 0, 1
 W_FP16, W_INT4_G128 = 0, 1
 
@@ -23,7 +23,7 @@ EXPORTS = [
     "pf_stack_step", "pf_plan_create", "pf_plan_run", "pf_plan_destroy", "pf_strerror",
     "pf_last_error", "pf_version", "pf_profile_begin", "pf_profile_end", "pf_dense_ffn",
     "pf_layer_step_auto", "pf_count_activations", "pf_ctx_set_lookahead", "pf_ctx_set_option",
-    "pf_ctx_get_option", "pf_ctx_set_mask_trace",
+    "pf_ctx_get_option", "pf_ctx_set_mask_trace", "pf_layer_step_noalloc",
 ]
 
 # pf_option keys
@@ -84,6 +84,8 @@ def lib():
         L.pf_ctx_set_option.argtypes = [P, I, I]
         L.pf_ctx_get_option.argtypes = [P, I, ctypes.POINTER(I)]
         L.pf_ctx_set_mask_trace.argtypes = [P, P, I]
+        L.pf_layer_step_noalloc.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(LayerWeights),
+                                            P, I, P, P]
         L.pf_stack_glue.argtypes = [P, P, P, I, I, P, P]
         L.pf_stack_step.argtypes = [P, PP, I, P, I, P, P]
         L.pf_plan_create.argtypes = [P, PP, I, P, I, P, P, PP]
@@ -306,6 +308,27 @@ class Plan:
             self.close()
         except Exception:
             pass
+
+
+def layer_step_noalloc(cfg, tensors, x, y, stream=None):
+    """pf_layer_step_noalloc on the current device: the layer step of the tensors of
+    workload.make_layer(cfg, ...) with the library's fixed scratch array, no context."""
+    g = tensors.get
+    wdt = torch.float16 if cfg.wtype == W_FP16 else torch.uint8
+    wn = cfg.ffn * cfg.d if cfg.wtype == W_FP16 else cfg.ffn * cfg.d // 2
+    desc = LayerDesc(cfg.d, cfg.ffn, cfg.r, cfg.act, cfg.wtype, cfg.threshold)
+    w = LayerWeights(
+        _dev_ptr(g("w_up"), wdt, wn), _dev_ptr(g("w_gate"), wdt, wn), _dev_ptr(g("w_down"), wdt, wn),
+        _dev_ptr(g("s_up"), torch.float16), _dev_ptr(g("s_gate"), torch.float16),
+        _dev_ptr(g("s_down"), torch.float16), _dev_ptr(g("b_up"), torch.float32, cfg.ffn),
+        _dev_ptr(g("b_down"), torch.float32, cfg.d), _dev_ptr(g("p1"), torch.float16, cfg.r * cfg.d),
+        _dev_ptr(g("p2"), torch.float16, cfg.ffn * cfg.r), _dev_ptr(g("p_bias"), torch.float32, cfg.ffn))
+    B = x.shape[0]
+    st = lib().pf_layer_step_noalloc(ctypes.byref(desc), ctypes.byref(w),
+                                     _dev_ptr(x, torch.float32, B * cfg.d), B,
+                                     _dev_ptr(y, torch.float32, B * cfg.d), _stream_ptr(stream))
+    if st != PF_OK:
+        raise PfError(st, lib().pf_strerror(st).decode())
 
 
 _hip = None

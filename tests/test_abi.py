@@ -31,8 +31,8 @@ def test_header_symbols_are_exported(pflib):
 def test_strerror_and_version(pflib):
     from paper_2312_12456_amd import pf
     assert pflib.pf_strerror(pf.PF_OK) == b"ok"
-    seen = {pflib.pf_strerror(s) for s in range(6)}
-    assert len(seen) == 6
+    seen = {pflib.pf_strerror(s) for s in range(7)}
+    assert len(seen) == 7
     assert b"gfx950" in pflib.pf_version()
 
 
@@ -62,6 +62,20 @@ def test_null_context_is_an_error_everywhere(pflib):
     pflib.pf_layer_destroy(None)
     pflib.pf_plan_destroy(None)
     assert pflib.pf_last_error(None) == b""
+
+
+def test_noalloc_entry_point_checks_its_limits_on_the_host(pflib):
+    """pf_layer_step_noalloc refuses null arguments and sizes beyond its fixed scratch array
+    before it touches a device."""
+    from paper_2312_12456_amd import pf
+    one = ctypes.c_void_p(256)  # never dereferenced
+    w = pf.LayerWeights(*([one] * 11))
+    assert pflib.pf_layer_step_noalloc(None, None, None, 1, None, None) == pf.PF_EINVAL
+    for d, ffn, r, B in ((8200, 1024, 64, 1), (1024, 32832, 64, 1), (1024, 1024, 2056, 1),
+                         (1024, 1024, 64, 5)):
+        desc = pf.LayerDesc(d, ffn, r, pf.ACT_RELU, pf.W_FP16, 0.5)
+        assert pflib.pf_layer_step_noalloc(ctypes.byref(desc), ctypes.byref(w), one, B, one,
+                                           None) == pf.PF_ELIMIT
 
 
 def test_product_package_does_not_touch_the_oracle():
