@@ -39,10 +39,12 @@ def parse_args():
     ap.add_argument("--config", default="opt-6.7b")
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--layers", type=int, default=None, help="override the layer count")
-    ap.add_argument("--mode", choices=["graph", "eager", "copycal", "m0"], default="graph",
+    ap.add_argument("--mode", choices=["graph", "eager", "copycal", "m0", "floors"], default="graph",
                     help="copycal: only run plain device copies of a known size, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters by; m0: operator "
-                         "micro-benchmark, one 4096 x 4096 layer, active fraction swept")
+                         "micro-benchmark, one 4096 x 4096 layer, active fraction swept; "
+                         "floors: latency-floor probes (empty kernel, dependent loads, plain "
+                         "streams from cache and from HBM, grid barrier) as graph nodes")
     ap.add_argument("--sort-neurons", type=int, default=0, metavar="N",
                     help="profile activation counts over N tokens first and lay every layer's "
                          "neurons out hot-first (frequency-sorted layout)")
@@ -101,6 +103,47 @@ def operator_microbench(args, torch, np, pf, wl):
             "random active rows, 64 launches per point", "points": rows}
 
 
+def latency_floors():
+    """Times of the probe kernels of libpf_probe.so as nodes of a replayed HIP graph (what a
+    kernel of the stack is: one node among ~100) and as eager launches stamped with events."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2312_12456_amd", "libpf_probe.so")
+    if not os.path.exists(path):
+        raise SystemExit("%s is missing: run __graft_entry__.build()" % path)
+    L = ctypes.CDLL(path)
+    D = ctypes.POINTER(ctypes.c_double)
+    L.pfp_measure.argtypes = [ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int, D, D, D]
+    L.pfp_last_error.restype = ctypes.c_char_p
+
+    def m(kind, size, grid, nodes=64, reps=20):
+        g, e, x = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+        if L.pfp_measure(kind, size, grid, nodes, reps, ctypes.byref(g), ctypes.byref(e), ctypes.byref(x)):
+            raise SystemExit("probe failed: %s" % L.pfp_last_error().decode())
+        return {"graph_node_us": round(g.value, 3), "eager_event_us": round(e.value, 3), "extra": round(x.value, 3)}
+
+    EMPTY, ONE, TWO, CHASE, STREAM, BARRIERS, EXCHANGE, STREAM_COLD, CHASE_COLD = range(9)
+    out = {"mode": "floors", "unit": "us", "rows": []}
+
+    def row(name, **kw):
+        kw["probe"] = name
+        out["rows"].append(kw)
+
+    row("empty kernel, 256 workgroups", **m(EMPTY, 0, 256))
+    row("one dependent load, 1024 workgroups", **m(ONE, 0, 1024))
+    row("two dependent loads, 1024 workgroups", **m(TWO, 0, 1024))
+    for mb in (8, 11, 32, 44, 64, 128):
+        row("stream %d MiB from HBM, 256 workgroups" % mb, **m(STREAM_COLD, mb << 20, 256, reps=10))
+    for mb in (8, 32):
+        row("stream %d MiB cache-resident, 256 workgroups" % mb, **m(STREAM, mb << 20, 256, nodes=32))
+    b0 = m(BARRIERS, 0, 256, nodes=8)
+    b32 = m(BARRIERS, 32, 256, nodes=8)
+    row("32 grid barriers in one launch of 256 workgroups (extra: us per barrier, device clock)", **b32)
+    row("the same launch without barriers", **b0)
+    row("8 rounds of 4 KB exchange per workgroup through 2 barriers (extra: mismatching words)",
+        **m(EXCHANGE, 8, 256, nodes=4, reps=5))
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -128,6 +171,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"mode": "copycal", "copies": 16, "bytes_read_per_copy": src.numel() * 4,
                           "bytes_written_per_copy": src.numel() * 4}))
+        return
+    if args.mode == "floors":
+        print(json.dumps(latency_floors()))
         return
     if args.mode == "m0":
         print(json.dumps(operator_microbench(args, torch, np, pf, wl)))

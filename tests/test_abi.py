@@ -28,6 +28,24 @@ def test_header_symbols_are_exported(pflib):
         assert hasattr(pflib, name), name
 
 
+def test_probe_library_exports_its_header():
+    """libpf_probe.so (latency-floor probes of the measurement harness) loads without a GPU and
+    exports what include/pf_probe.h declares."""
+    from paper_2312_12456_amd import build
+    if not os.path.exists(build.PROBE_LIB):
+        build.build_probe()
+    lib = ctypes.CDLL(build.PROBE_LIB)
+    text = open(os.path.join(ROOT, "include", "pf_probe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(pfp_[a-z_]+)\s*\(", text))
+    assert declared == {"pfp_measure", "pfp_last_error"}
+    for name in declared:
+        assert hasattr(lib, name), name
+    lib.pfp_measure.argtypes = [ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.pfp_measure(0, 0, 256, 1, 1, None, None, None) == 1   # null outputs: refused
+
+
 def test_strerror_and_version(pflib):
     from paper_2312_12456_amd import pf
     assert pflib.pf_strerror(pf.PF_OK) == b"ok"
