@@ -3,7 +3,9 @@
  *
  * TEST INFRASTRUCTURE ONLY.  Nothing on the product path may include, link or call
  * this file; only the tests, the smoke check and the benchmark's cpu_baseline leg do.
- * It shares no code, header, table or constant with the HIP library.
+ * It shares no code, header or table with the HIP library.  (The integer-mix constants of
+ * the benchmark glue's sign pattern are, necessarily, written out on both sides: they define
+ * the pattern.)
  *
  * What it states (PowerInfer, arXiv 2312.12456):
  *   - A neuron is one row of FC1 (and of the gate matrix for gated FFNs) together with
@@ -48,7 +50,8 @@ typedef struct {
     int32_t d;         /* model width                                              */
     int32_t ffn;       /* number of neurons F                                      */
     int32_t r;         /* predictor hidden width                                   */
-    int32_t act;       /* 0: ReLU FFN with FC1 bias; 1: ReLU-gated (gate, up, down)*/
+    int32_t act;       /* 0: ReLU FFN with FC1 bias; 1: ReLU-gated (gate, up, down);
+                          2: dReLU (ReLU on the gate and on the up branch)         */
     int32_t wtype;     /* 0: fp16 bit patterns; 1: int4, group 128, fp16 scales    */
     int32_t pad_;
     double threshold;  /* predictor score threshold tau                            */
@@ -131,6 +134,10 @@ static double dot_row(const double *wrow, const float *x, int d)
  * neuron hands to FC2.  *pre is the quantity whose sign decides "activated":
  *   ReLU FFN : pre = w_up[i].x + b_up[i],            h = max(pre, 0)
  *   gated    : pre = w_gate[i].x + b_up[i] (gate),   h = max(pre, 0) * (w_up[i].x)
+ *   dReLU    : g = w_gate[i].x + b_up[i], u = w_up[i].x,  h = max(g, 0) * max(u, 0),
+ *              pre = min(g, u): the neuron contributes only when both branches are open
+ *              (the activation of the Bamboo-7B row of Table "model_eval", Sec. 8.1; the
+ *              paper names it without a formula, this is the reading taken)
  */
 static double neuron_fc1(const pfo_layer *L, int i, const float *x, double *rowbuf, double *pre)
 {
@@ -146,6 +153,10 @@ static double neuron_fc1(const pfo_layer *L, int i, const float *x, double *rowb
     double g = dot_row(rowbuf, x, d) + bias;
     widen_row(L, L->w_up, L->s_up, i, 0, d, rowbuf);
     double u = dot_row(rowbuf, x, d);
+    if (L->act == 2) {
+        *pre = g < u ? g : u;
+        return (g > 0.0 ? g : 0.0) * (u > 0.0 ? u : 0.0);
+    }
     *pre = g;
     return (g > 0.0 ? g : 0.0) * u;
 }

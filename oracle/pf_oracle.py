@@ -19,6 +19,7 @@ _LIB = os.path.join(_HERE, "libpf_oracle.so")
 
 ACT_RELU = 0
 ACT_REGLU = 1
+ACT_DRELU = 2
 W_FP16 = 0
 W_INT4_G128 = 1
 
@@ -123,8 +124,8 @@ def _f32(a, shape):
 class Layer:
     """One FFN layer with its predictor, held as host arrays for the oracle.
 
-    act: ACT_RELU (w_up, b_up, w_down, b_down) or ACT_REGLU (w_gate, b_up = gate bias,
-    w_up, w_down).  w_down is FC2 transposed: [ffn][d].  For W_INT4_G128 the w_* are
+    act: ACT_RELU (w_up, b_up, w_down, b_down), ACT_REGLU or ACT_DRELU (w_gate, b_up = gate
+    bias, w_up, w_down).  w_down is FC2 transposed: [ffn][d].  For W_INT4_G128 the w_* are
     uint8 [ffn][d/2] and s_* float16 [ffn][d/128].
     """
 
@@ -156,7 +157,7 @@ class Layer:
         keep["p1"] = None if p1 is None else _bits16(p1, (r, d))
         keep["p2"] = None if p2 is None else _bits16(p2, (ffn, r))
         keep["p_bias"] = None if p_bias is None else _f32(p_bias, (ffn,))
-        if act == ACT_REGLU and w_up is not None:
+        if act != ACT_RELU and w_up is not None:
             assert keep["w_gate"] is not None
         if wtype == W_INT4_G128:
             for k in ("up", "gate", "down"):

@@ -33,6 +33,7 @@ from scipy.special import ndtri
 
 ACT_RELU = 0
 ACT_REGLU = 1
+ACT_DRELU = 2
 W_FP16 = 0
 W_INT4_G128 = 1
 
@@ -56,7 +57,7 @@ class StackConfig:
 
     @property
     def n_matrices(self):
-        return 3 if self.act == ACT_REGLU else 2
+        return 2 if self.act == ACT_RELU else 3
 
     @property
     def row_bytes(self):
@@ -80,6 +81,10 @@ CONFIGS = {
                            0.06, 1.3, 256, (1, 4, 8)),
     "opt-175b-int4": StackConfig("opt-175b-int4", 96, 12288, 49152, 2048, ACT_RELU,
                                  W_INT4_G128, 0.04, 1.3, 256, (1,)),
+    # the dReLU model of the paper's list (Bamboo-7B: a Mistral-7B-shaped gated FFN with ReLU
+    # on both branches, 90 % sparsity in the model table)
+    "bamboo-7b-drelu": StackConfig("bamboo-7b-drelu", 32, 4096, 14336, 1024, ACT_DRELU, W_FP16,
+                                   0.10, 1.2, 256, (1,)),
     # a second OPT-like shape beside the benchmark configurations: the ReLU Falcon-40B FFN
     # (95 % sparsity in the paper's model table), 60 layers
     "falcon-40b-relu": StackConfig("falcon-40b-relu", 60, 8192, 32768, 1024, ACT_RELU, W_FP16,
@@ -182,14 +187,17 @@ def make_layer(cfg, layer, seed, device="cpu", pred_bias=True):
     device = torch.device(device)
     p = zipf_probabilities(cfg.ffn, cfg.alpha, cfg.rate, _seed64(seed, "layer", layer))
     out = {"p": p}
-    names = ["w_up", "w_down"] + (["w_gate"] if cfg.act == ACT_REGLU else [])
+    names = ["w_up", "w_down"] + (["w_gate"] if cfg.act != ACT_RELU else [])
     for nm in names:
         w, s = _weight_matrix(cfg, device, _generator(device, seed, "layer", layer, nm))
         out[nm] = w
         if s is not None:
             out["s_" + nm[2:]] = s
     quant = ndtri(p)
-    out["b_up"] = torch.from_numpy(quant.astype(np.float32)).to(device)
+    # dReLU: a neuron fires when the gate AND the (bias-free, sign-symmetric) up branch are
+    # positive, so the gate is opened twice as often to keep the firing rate at p_i
+    gate_quant = ndtri(np.minimum(P_MAX, 2.0 * p)) if cfg.act == ACT_DRELU else quant
+    out["b_up"] = torch.from_numpy(gate_quant.astype(np.float32)).to(device)
     if cfg.act == ACT_RELU:
         g = _generator("cpu", seed, "layer", layer, "b_down")
         out["b_down"] = (torch.randn(cfg.d, generator=g, dtype=torch.float32) * 0.1).to(device)

@@ -20,10 +20,10 @@ def _rand_layer(oracle, d, F, r, act, seed, wtype=wl.W_FP16, with_bias=True):
     rng = np.random.default_rng(seed)
     kw = {}
     if wtype == wl.W_FP16:
-        for nm in ("w_up", "w_down") + (("w_gate",) if act == wl.ACT_REGLU else ()):
+        for nm in ("w_up", "w_down") + (("w_gate",) if act != wl.ACT_RELU else ()):
             kw[nm] = (rng.standard_normal((F, d)) / np.sqrt(d)).astype(np.float16)
     else:
-        for nm in ("up", "down") + (("gate",) if act == wl.ACT_REGLU else ()):
+        for nm in ("up", "down") + (("gate",) if act != wl.ACT_RELU else ()):
             kw["w_" + nm] = rng.integers(0, 256, (F, d // 2), dtype=np.uint8)
             kw["s_" + nm] = (rng.uniform(0.01, 0.05, (F, d // 128))).astype(np.float16)
     if with_bias:
@@ -59,7 +59,7 @@ def test_half_conversion_all_bit_patterns(oracle):
 
 
 # ------------------------------------------------- I5: library matmul, closed forms
-@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU, wl.ACT_DRELU])
 @pytest.mark.parametrize("B", [1, 3])
 def test_dense_ffn_matches_fp64_matmul(oracle, act, B):
     d, F, r = 96, 160, 16
@@ -70,9 +70,14 @@ def test_dense_ffn_matches_fp64_matmul(oracle, act, B):
     if act == wl.ACT_RELU:
         pre = X @ Wu.T + kw["b_up"].astype(np.float64)
         h = np.maximum(pre, 0)
-    else:
+    elif act == wl.ACT_REGLU:
         pre = X @ kw["w_gate"].astype(np.float64).T + kw["b_up"].astype(np.float64)
         h = np.maximum(pre, 0) * (X @ Wu.T)
+    else:
+        g = X @ kw["w_gate"].astype(np.float64).T + kw["b_up"].astype(np.float64)
+        u = X @ Wu.T
+        pre = np.minimum(g, u)
+        h = np.maximum(g, 0) * np.maximum(u, 0)
     y = h @ Wd + kw["b_down"].astype(np.float64)
     np.testing.assert_allclose(L.preact(x), pre, rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(L.dense_ffn(x), y, rtol=1e-11, atol=1e-12)
@@ -94,6 +99,35 @@ def test_fc2_is_not_transposed_or_unbiased(oracle):
     assert np.array_equal(L.dense_ffn(x)[0], want)
     x[0, 5] = -3.0                         # ReLU closes the neuron: only the bias is left
     assert np.array_equal(L.dense_ffn(x)[0], np.full(d, 10.0))
+
+
+def test_drelu_closes_on_either_branch(oracle):
+    """dReLU (ReLU on the gate branch and on the up branch; the Bamboo-7B row of the paper's
+    model table): one neuron whose gate reads x[0] and whose up branch reads x[1].  It
+    contributes g * u only when both are positive; the plain gated form differs exactly where
+    the up branch is negative."""
+    d, F, r = 8, 2, 2
+    w_gate = np.zeros((F, d), np.float16)
+    w_up = np.zeros((F, d), np.float16)
+    w_down = np.zeros((F, d), np.float16)
+    w_gate[1, 0] = 1.0
+    w_up[1, 1] = 1.0
+    w_down[1, :] = 1.0
+    for gx, ux in ((2.0, 3.0), (2.0, -3.0), (-2.0, 3.0), (-2.0, -3.0)):
+        x = np.zeros((1, d), np.float32)
+        x[0, 0], x[0, 1] = gx, ux
+        both = max(gx, 0.0) * max(ux, 0.0)
+        kw = dict(w_gate=w_gate, w_up=w_up, w_down=w_down, b_up=np.zeros(F, np.float32))
+        Ld = oracle.Layer(d, F, r, act=wl.ACT_DRELU, **kw)
+        Lg = oracle.Layer(d, F, r, act=wl.ACT_REGLU, **kw)
+        assert np.array_equal(Ld.dense_ffn(x)[0], np.full(d, both))
+        assert np.array_equal(Lg.dense_ffn(x)[0], np.full(d, max(gx, 0.0) * ux))
+        assert Ld.exact_mask(x).tolist() == [False, gx > 0 and ux > 0]
+        assert Lg.exact_mask(x).tolist() == [False, gx > 0]
+        # with a gate bias: the bias belongs to the gate branch only
+        kw["b_up"] = np.array([0.0, 5.0], np.float32)
+        Lb = oracle.Layer(d, F, r, act=wl.ACT_DRELU, **kw)
+        assert np.array_equal(Lb.dense_ffn(x)[0], np.full(d, max(gx + 5.0, 0.0) * max(ux, 0.0)))
 
 
 def test_predictor_matches_fp64_matmul_and_threshold_is_strict(oracle):
@@ -141,7 +175,7 @@ def test_predictor_selector_special_case(oracle):
 
 
 # -------------------------------------------- I1, I2, I3, I8: the paper's identities
-@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU, wl.ACT_DRELU])
 @pytest.mark.parametrize("wtype", [wl.W_FP16, wl.W_INT4_G128])
 def test_mask_identities(oracle, act, wtype):
     d, F, r = 128, 192, 16
@@ -171,8 +205,11 @@ def test_mask_identities(oracle, act, wtype):
     X = x.astype(np.float64)
     if act == wl.ACT_RELU:
         h_i = np.maximum(pre[:, i], 0)
-    else:
+    elif act == wl.ACT_REGLU:
         h_i = np.maximum(pre[:, i], 0) * (X @ Wu[i])
+    else:
+        Wg = _widen(oracle, L, kw, "gate")
+        h_i = np.maximum(X @ Wg[i] + float(kw["b_up"][i]), 0) * np.maximum(X @ Wu[i], 0)
     np.testing.assert_allclose(dense - L.masked_ffn(x, fn), np.outer(h_i, Wd[i]),
                                rtol=1e-9, atol=1e-12)
     # empty mask leaves the FC2 bias
@@ -242,13 +279,15 @@ def _brute_force(act, W_up, W_gate, W_dT, b_up, b_down, x, mask):
         else:
             g = sum(int(W_gate[i][c]) * int(x[c]) for c in range(d)) + int(b_up[i])
             u = sum(int(W_up[i][c]) * int(x[c]) for c in range(d))
+            if act == wl.ACT_DRELU and u < 0:
+                u = 0
             h = (g if g > 0 else 0) * u
         for c in range(d):
             y[c] += h * int(W_dT[i][c])
     return y
 
 
-@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU, wl.ACT_DRELU])
 def test_brute_force_all_masks_tiny_layer(oracle, act):
     d, F, r = 6, 9, 2
     rng = np.random.default_rng(77 + act)
@@ -414,7 +453,8 @@ def test_workload_is_seeded_and_layers_differ():
 def test_neuron_permutation_leaves_the_function_unchanged(oracle):
     """Renumbering the neurons (frequency-sorted layout) permutes the predictor's mask and
     leaves dense, masked and predicted-mask outputs unchanged up to the order of an fp64 sum."""
-    for act, wtype in ((wl.ACT_RELU, wl.W_FP16), (wl.ACT_REGLU, wl.W_FP16), (wl.ACT_RELU, wl.W_INT4_G128)):
+    for act, wtype in ((wl.ACT_RELU, wl.W_FP16), (wl.ACT_REGLU, wl.W_FP16), (wl.ACT_RELU, wl.W_INT4_G128),
+                       (wl.ACT_DRELU, wl.W_FP16)):
         cfg = small_cfg(d=256, ffn=320, r=48, act=act, wtype=wtype, rate=0.2)
         lay = wl.to_host(wl.make_layer(cfg, 0, seed=5))
         order = np.random.Generator(np.random.PCG64(3)).permutation(cfg.ffn)
