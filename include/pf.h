@@ -44,7 +44,10 @@ typedef enum {
 
 typedef enum {
     PF_ACT_RELU = 0,  /* OPT-style: h = ReLU(w_up.x + b_up)                      (Sec. 2.1) */
-    PF_ACT_REGLU = 1  /* ReLU-gated: h = ReLU(w_gate.x + b_up) * (w_up.x)  (Table "model_eval") */
+    PF_ACT_REGLU = 1, /* ReLU-gated: h = ReLU(w_gate.x + b_up) * (w_up.x)  (Table "model_eval") */
+    PF_ACT_DRELU = 2  /* dReLU: h = ReLU(w_gate.x + b_up) * ReLU(w_up.x): the activation named for
+                         Bamboo-7B in Table "model_eval"; the paper gives no formula, this is
+                         the reading taken (ReLU on both branches of the gated block)          */
 } pf_act;
 
 typedef enum {
@@ -65,7 +68,7 @@ typedef struct {
 
 typedef struct {
     const void *w_up;    /* [ffn][d] fp16, or [ffn][d/2] packed int4                     */
-    const void *w_gate;  /* same shape; NULL unless act == PF_ACT_REGLU                  */
+    const void *w_gate;  /* same shape; NULL for PF_ACT_RELU, required otherwise          */
     const void *w_down;  /* FC2 transposed, [ffn][d] / [ffn][d/2]                        */
     const void *s_up;    /* [ffn][d/128] fp16 scales, int4 only, else NULL               */
     const void *s_gate;

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kPredOutThreads) void k_out_up(
     const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
     const float *__restrict__ b_up, const float *__restrict__ x, int r, int d, int ffn, int hs,
     float thr_logit, bool strided, uint64_t *__restrict__ seg_words,
-    uint8_t *__restrict__ seg_pos, float *__restrict__ h)
+    uint8_t *__restrict__ seg_pos, float *__restrict__ h, float up_floor)
 {
     extern __shared__ float ts[];  // [B][rpad] hidden vector, then [B][dpad] layer input
     static_assert(kPredOutNeurons == 64, "one mask word per block");
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(kPredOutThreads) void k_out_up(
             if (GATED) {
                 const float gsum = wave_sum(ag[b]) + bias;
                 const float usum = wave_sum(au[b]);
-                v = fmaxf(gsum, 0.f) * usum;
+                v = fmaxf(gsum, 0.f) * fmaxf(usum, up_floor);
             } else {
                 v = fmaxf(wave_sum(au[b]) + bias, 0.f);
             }

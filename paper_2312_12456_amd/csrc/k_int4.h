@@ -116,7 +116,7 @@ __global__ __launch_bounds__(kUpI4Threads) void k_up_i4(
     const float *__restrict__ b_up, const float *__restrict__ x,
     const int32_t *__restrict__ idx_in, const int32_t *__restrict__ count_in,
     const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
-    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn)
+    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor)
 {
     extern __shared__ float xs[];
     __shared__ uint32_t wave_tot[kUpI4Waves];
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(kUpI4Threads) void k_up_i4(
             if (GATED) {
                 const float gsum = wave_sum(ag[b]) + bias;
                 const float usum = wave_sum(au[b]);
-                v = fmaxf(gsum, 0.f) * usum;
+                v = fmaxf(gsum, 0.f) * fmaxf(usum, up_floor);
             } else {
                 v = fmaxf(wave_sum(au[b]) + bias, 0.f);
             }

@@ -94,6 +94,7 @@ struct UpMfmaArgs {
     int *irow;
     float *brow;
     int B, hs, d, ffn, n, nwords, top_step, j_begin, j_end;
+    float up_floor;  // gated forms: lower clamp of the up branch (-infinity, or 0 for dReLU)
 };
 
 // The list slots [j_begin, j_end) of a block in passes of R rows (R / 16 MFMA tiles).
@@ -231,7 +232,7 @@ __device__ __forceinline__ void up_mfma_passes(const UpMfmaArgs &a)
             const int i = a.irow[row];
             const int j = j0 + row;
             const float bias = a.brow[row];  // fetched when the row was selected
-            const float v = GATED ? fmaxf(sg + bias, 0.f) * su : fmaxf(su + bias, 0.f);
+            const float v = GATED ? fmaxf(sg + bias, 0.f) * fmaxf(su, a.up_floor) : fmaxf(su + bias, 0.f);
             if (colb < a.B && j < a.j_end) a.h[(size_t)j * a.hs + colb] = i >= 0 ? v : 0.f;
         }
         __syncthreads();
@@ -252,7 +253,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     const float *__restrict__ b_up, const float *__restrict__ x, int B,
     const int32_t *__restrict__ idx_in, const int32_t *__restrict__ count_in,
     const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
-    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn)
+    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor)
 {
     extern __shared__ uint64_t dyn_lds64[];
     __shared__ uint32_t wave_tot[kMfmaWaves];
@@ -295,6 +296,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     a.n = n;
     a.nwords = nwords;
     a.top_step = top_step;
+    a.up_floor = up_floor;
     const int rpb = (n + (int)gridDim.x - 1) / (int)gridDim.x;
     a.j_begin = min(n, (int)blockIdx.x * rpb);
     a.j_end = min(n, a.j_begin + rpb);

@@ -29,13 +29,15 @@ inline size_t up_mask_lds_bytes(int ffn)
 // words (popcount prefix in LDS, then each wave selects its j-th set bit), writes the
 // entries it owns to idx_out and block 0 writes the count -- the compaction fused into its
 // consumer, so the layer step needs no separate compaction launch.
+// Gated forms (ACT == 1): h = ReLU(gate . x + bias) * max(up . x, up_floor); up_floor is
+// -infinity for the plain ReLU-gated block and 0 for dReLU (ReLU on both branches).
 template <int B, int ACT, bool FROM_MASK>
 __global__ __launch_bounds__(kUpThreads) void k_up(
     const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
     const float *__restrict__ b_up, const float *__restrict__ x,
     const int32_t *__restrict__ idx_in, const int32_t *__restrict__ count_in,
     const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
-    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn)
+    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor)
 {
     extern __shared__ float xs[];
     __shared__ uint32_t wave_tot[kUpWaves];
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
             if (GATED) {
                 const float gsum = wave_sum(ag[b]) + bias;
                 const float usum = wave_sum(au[b]);
-                v = fmaxf(gsum, 0.f) * usum;
+                v = fmaxf(gsum, 0.f) * fmaxf(usum, up_floor);
             } else {
                 v = fmaxf(wave_sum(au[b]) + bias, 0.f);
             }

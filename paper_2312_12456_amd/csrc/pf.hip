@@ -119,6 +119,8 @@ pf_status fail(pf_ctx *ctx, pf_status s, const char *fmt, ...)
     } while (0)
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+// Lower clamp of the up branch in the gated kernels: none for the ReLU-gated block, 0 for dReLU.
+inline float up_floor_of(const pf_layer_desc &D) { return D.act == PF_ACT_DRELU ? 0.f : -INFINITY; }
 inline float logit_of(float tau) { return (float)std::log((double)tau / (1.0 - (double)tau)); }
 inline int kpad_of(int k) { return cdiv(k, pf::kChunk) * pf::kChunk; }
 
@@ -373,7 +375,7 @@ pf_status launch_sparse_i4(pf_ctx *ctx, const pf_layer *L, const float *x, int B
     if (tile > B) tile = B;
     int up_grid = cdiv(D.ffn, pf::kUpI4Waves);
     if (up_grid > ctx->up_grid_cap_i4) up_grid = ctx->up_grid_cap_i4;
-    const bool gated = D.act == PF_ACT_REGLU;
+    const bool gated = D.act != PF_ACT_RELU;
     for (int b0 = 0; b0 < B; b0 += tile) {
         const int bt = (B - b0) < tile ? (B - b0) : tile;
         const size_t lds = (size_t)bt * per_tok + pf::kStageScrap * sizeof(float) + extra;
@@ -384,7 +386,7 @@ pf_status launch_sparse_i4(pf_ctx *ctx, const pf_layer *L, const float *x, int B
     PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_up_i4<BT, ACT, FM>), dim3(up_grid),                      \
                               dim3(pf::kUpI4Threads), lds, st, q_up, s_up, q_gate, s_gate,        \
                               L->w.b_up, xb, idx_in, count_in, mask_words, ctx->idx, ctx->count,  \
-                              hb, pf::h_stride(B), D.d, D.ffn))
+                              hb, pf::h_stride(B), D.d, D.ffn, up_floor_of(D)))
         if (gated && from_mask) { PF_UP4(1, true); }
         else if (gated) { PF_UP4(1, false); }
         else if (from_mask) { PF_UP4(0, true); }
@@ -433,7 +435,7 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     const bool from_mask = mask_words != nullptr;
     const size_t extra = from_mask ? pf::up_mask_lds_bytes(D.ffn) : 0;
     const int tile = batch_tile(ctx, D.d, B, extra + 1024);
-    const bool gated = D.act == PF_ACT_REGLU;
+    const bool gated = D.act != PF_ACT_RELU;
     int up_grid = cdiv(D.ffn, pf::kUpWaves);
     if (up_grid > ctx->up_grid_cap) up_grid = ctx->up_grid_cap;
     const size_t mfma_lds = pf::up_mfma_lds_bytes(D.ffn, from_mask, gated);
@@ -446,7 +448,7 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
 #define PF_UPM(ACT, FM)                                                                           \
     PF_LAUNCH(ps, (pf::k_up_mfma<ACT, FM>), dim3(grid), dim3(pf::kMfmaThreads), mfma_lds, st, w_up, \
               w_gate, L->w.b_up, x, B, idx_in, count_in, mask_words, ctx->idx, ctx->count, ctx->h, \
-              pf::h_stride(B), D.d, D.ffn)
+              pf::h_stride(B), D.d, D.ffn, up_floor_of(D))
         if (gated && from_mask) { PF_UPM(1, true); }
         else if (gated) { PF_UPM(1, false); }
         else if (from_mask) { PF_UPM(0, true); }
@@ -463,7 +465,7 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_up<BT, ACT, FM>), dim3(up_grid),                    \
                                        dim3(pf::kUpThreads), lds, st, w_up, w_gate, L->w.b_up, xb, \
                                        idx_in, count_in, mask_words, ctx->idx, ctx->count, hb,    \
-                                       pf::h_stride(B), D.d, D.ffn))
+                                       pf::h_stride(B), D.d, D.ffn, up_floor_of(D)))
         if (gated && from_mask) { PF_UP(1, true); }
         else if (gated) { PF_UP(1, false); }
         else if (from_mask) { PF_UP(0, true); }
@@ -525,7 +527,7 @@ bool fused_ok(const pf_ctx *ctx, const pf_layer *L, int B)
     // slow) and loses 1 - 7 % with long rows at batch 1, where FC1 and FC2 are long enough
     // for the uneven work per segment to cost more than the boundary.  (Three tokens with
     // long rows never get here: mfma_from sends them to the matrix cores.)
-    const bool gated = D.act == PF_ACT_REGLU;
+    const bool gated = D.act != PF_ACT_RELU;
     return B == 3 || D.d <= 4096 || (B == 2 && !gated);
 }
 
@@ -542,7 +544,7 @@ pf_status launch_layer_fused(pf_ctx *ctx, const pf_layer *L, const float *x, con
     const __half *w_up = static_cast<const __half *>(L->w.w_up);
     const __half *w_gate = static_cast<const __half *>(L->w.w_gate);
     const __half *w_down = static_cast<const __half *>(L->w.w_down);
-    const bool gated = D.act == PF_ACT_REGLU;
+    const bool gated = D.act != PF_ACT_RELU;
     const size_t lds = pf::out_up_lds_bytes(B, D.r, D.d);
     {
         ProfScope ps(ctx, K_OUT_UP);
@@ -552,7 +554,7 @@ pf_status launch_layer_fused(pf_ctx *ctx, const pf_layer *L, const float *x, con
                              (const float *)ctx->t, w_up, w_gate, L->w.b_up, x_in, D.r, D.d,      \
                              D.ffn, pf::h_stride(B), L->thr_logit, ctx->seg_strided != 0,         \
                              ctx->mask_words2,                                                    \
-                             reinterpret_cast<uint8_t *>(ctx->idx), ctx->h))
+                             reinterpret_cast<uint8_t *>(ctx->idx), ctx->h, up_floor_of(D)))
         if (gated) { PF_OU(1); } else { PF_OU(0); }
 #undef PF_OU
     }
@@ -758,7 +760,7 @@ pf_status check_layer(pf_ctx *ctx, const pf_layer_desc *desc, const pf_layer_wei
         return fail(ctx, PF_EINVAL, "non-positive size");
     if (!(desc->threshold > 0.f && desc->threshold < 1.f))
         return fail(ctx, PF_EINVAL, "threshold %g outside (0,1)", (double)desc->threshold);
-    if (desc->act != PF_ACT_RELU && desc->act != PF_ACT_REGLU)
+    if (desc->act != PF_ACT_RELU && desc->act != PF_ACT_REGLU && desc->act != PF_ACT_DRELU)
         return fail(ctx, PF_EUNSUPPORTED, "activation %d", desc->act);
     if (desc->wtype != PF_W_FP16 && desc->wtype != PF_W_INT4_G128)
         return fail(ctx, PF_EUNSUPPORTED, "weight type %d", desc->wtype);
@@ -774,11 +776,11 @@ pf_status check_layer(pf_ctx *ctx, const pf_layer_desc *desc, const pf_layer_wei
     if ((uint64_t)desc->ffn * desc->d * 2 >= (1ull << 32) || (uint64_t)desc->ffn * desc->r * 2 >= (1ull << 32))
         return fail(ctx, PF_ESHAPE, "a weight matrix of 4 GiB or more is not supported");
     if (!w->w_up || !w->w_down) return fail(ctx, PF_EINVAL, "w_up / w_down is null");
-    if (desc->act == PF_ACT_REGLU && !w->w_gate) return fail(ctx, PF_EINVAL, "gated layer without w_gate");
+    if (desc->act != PF_ACT_RELU && !w->w_gate) return fail(ctx, PF_EINVAL, "gated layer without w_gate");
     if ((w->p1 == nullptr) != (w->p2 == nullptr))
         return fail(ctx, PF_EINVAL, "p1 and p2 must both be given or both be null");
     if (desc->wtype == PF_W_INT4_G128) {
-        if (!w->s_up || !w->s_down || (desc->act == PF_ACT_REGLU && !w->s_gate))
+        if (!w->s_up || !w->s_down || (desc->act != PF_ACT_RELU && !w->s_gate))
             return fail(ctx, PF_EINVAL, "int4 layer without scales");
     }
     return PF_OK;

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("PF_LIB_PATH") or os.path.join(_HERE, "libpf.so")
 
 PF_OK, PF_EINVAL, PF_ESHAPE, PF_ENOMEM, PF_EHIP, PF_EUNSUPPORTED, PF_ELIMIT = range(7)
-ACT_RELU, ACT_REGLU = 0, 1
+ACT_RELU, ACT_REGLU, ACT_DRELU = 0, 1, 2
 W_FP16, W_INT4_G128 = 0, 1
 
 EXPORTS = [

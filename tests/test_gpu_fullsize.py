@@ -38,6 +38,7 @@ def _mask_of(pf, ctx, ffn):
     ("llama2-13b-reglu", 1, 0), ("llama2-13b-reglu", 4, 20),
     ("opt-30b", 1, 0), ("opt-30b", 8, 47), ("opt-30b", 4, 24), ("opt-30b", 3, 1),
     ("falcon-40b-relu", 1, 0), ("falcon-40b-relu", 1, 59),
+    ("bamboo-7b-drelu", 1, 0), ("bamboo-7b-drelu", 1, 31), ("bamboo-7b-drelu", 4, 16),
     ("opt-175b-int4", 1, 0), ("opt-175b-int4", 1, 95),
 ])
 def test_full_shape_layer_step(pf, oracle, name, B, layer):
@@ -94,7 +95,8 @@ def test_full_shape_stack_plan_matches_layer_chain(pf):
     plan.close()
 
 
-@pytest.mark.parametrize("name,B", [("opt-6.7b", 1), ("opt-6.7b", 3), ("opt-30b", 2)])
+@pytest.mark.parametrize("name,B", [("opt-6.7b", 1), ("opt-6.7b", 3), ("opt-30b", 2),
+                                    ("bamboo-7b-drelu", 1)])
 def test_full_shape_stack_three_launch_form_matches_oracle(pf, oracle, name, B):
     """Three full-size layers through the recorded plan, at the shapes and batches where the
     stack's inner layers take the three-launch form (output layer + FC1 fused, FC2 over

@@ -41,7 +41,7 @@ CASES = [
 
 
 @pytest.mark.parametrize("strided", [0, 1])
-@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU, wl.ACT_DRELU])
 @pytest.mark.parametrize("B", [1, 2, 3])
 @pytest.mark.parametrize("case", range(len(CASES)))
 def test_fused_stack_matches_oracle_and_list_form(pf, oracle, case, B, act, strided):

@@ -95,7 +95,7 @@ def test_compact_bit_exact(pf, oracle, ffn, density):
     assert np.array_equal(idx.cpu().numpy()[:n], ref)
 
 
-@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU, wl.ACT_DRELU])
 @pytest.mark.parametrize("shape", SHAPES)
 @pytest.mark.parametrize("B", [1, 2, 5, 8])
 def test_sparse_ffn_exact_mask(pf, oracle, act, shape, B):
@@ -164,7 +164,7 @@ def test_sparse_ffn_degenerate_lists(pf, oracle, act):
     check_output(y.cpu().numpy(), O.masked_ffn(xh, m), "skip invalid")
 
 
-@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU, wl.ACT_DRELU])
 @pytest.mark.parametrize("shape", SHAPES)
 @pytest.mark.parametrize("B", [1, 4])
 def test_layer_step_predicted_mask(pf, oracle, act, shape, B):
@@ -287,9 +287,13 @@ def test_argument_errors_reach_the_caller(pf):
     with pytest.raises(pf.PfError) as e:
         pf.Layer(ctx, 1024, 1344, 136, w_up=big, w_down=big)   # wider than the context
     assert e.value.status == pf.PF_ESHAPE
+    for gated in (pf.ACT_REGLU, pf.ACT_DRELU):   # a gated layer needs its gate matrix
+        with pytest.raises(pf.PfError) as e:
+            pf.Layer(ctx, 520, 1344, 136, act=gated, w_up=lay["w_up"], w_down=lay["w_down"])
+        assert e.value.status == pf.PF_EINVAL
     with pytest.raises(pf.PfError) as e:
-        pf.Layer(ctx, 520, 1344, 136, act=pf.ACT_REGLU, w_up=lay["w_up"], w_down=lay["w_down"])
-    assert e.value.status == pf.PF_EINVAL
+        pf.Layer(ctx, 520, 1344, 136, act=3, w_up=lay["w_up"], w_down=lay["w_down"])
+    assert e.value.status == pf.PF_EUNSUPPORTED
 
 
 INT4_SHAPES = [
@@ -299,7 +303,7 @@ INT4_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU, wl.ACT_DRELU])
 @pytest.mark.parametrize("shape", INT4_SHAPES)
 @pytest.mark.parametrize("B", [1, 3])
 def test_int4_exact_mask_and_layer_step(pf, oracle, act, shape, B):
@@ -340,7 +344,7 @@ def test_int4_exact_mask_and_layer_step(pf, oracle, act, shape, B):
     assert torch.equal(y, y2)
 
 
-@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU, wl.ACT_DRELU])
 @pytest.mark.parametrize("d", [800, 2080])          # 25 and 65 K-steps of 32: ragged unroll tails
 @pytest.mark.parametrize("B", [4, 7, 8])
 def test_fc1_on_matrix_cores_matches_oracle_and_vector_path(pf, oracle, act, d, B):
