@@ -188,9 +188,12 @@ pf_status pf_ctx_last_active(pf_ctx *ctx, const uint64_t **mask_words, const int
 /* Look-ahead prediction (Sec. 2.1: the activations of a layer can be predicted a few layers
  * ahead, from an earlier layer's input).  With distance 1, pf_stack_step and the plans
  * created afterwards take the active set of layer l >= 1 from layer l's predictor applied to
- * the INPUT of layer l-1 (layer 0: its own input), and run the predictors on a second stream
- * of the library beside the sparse kernels of the layer before, so that a layer costs
- * max(predictor, sparse FFN) instead of their sum.  This changes which neurons are listed
+ * the INPUT of layer l-1 (layer 0: its own input), so that the predictor of layer l and the
+ * sparse kernels of layer l-1 are independent and a layer costs about max(predictor, sparse
+ * FFN) instead of their sum.  With fp16 weights up to batch 3 a layer then runs as two
+ * launches whose block ranges play two roles (hidden layer of the next predictor beside FC1;
+ * FC2 beside the next predictor's output layer); otherwise the predictors run on a second
+ * stream of the library beside the sparse kernels of the layer before.  This changes which neurons are listed
  * (an approximation whose accuracy depends on trained predictors and is not measured here);
  * every other call is unaffected.  distance: 0 (off, the default) or 1. */
 pf_status pf_ctx_set_lookahead(pf_ctx *ctx, int distance);
@@ -210,6 +213,8 @@ pf_status pf_ctx_set_lookahead(pf_ctx *ctx, int distance);
  *   PF_OPT_UP_GRID          workgroups of the vector FC1 kernel (default 8 per CU; int4: 2)
  *   PF_OPT_MFMA_GRID        workgroups of the matrix-core FC1 kernel (default one per CU)
  *   PF_OPT_DOWN_SPLIT       row groups of FC2, 1 .. 4 (default CUs / column tiles, at most 4)
+ *   PF_OPT_LOOKAHEAD_MERGED look-ahead stacks in two launches per layer where that form applies
+ *                           (see pf_ctx_set_lookahead): 1 (default) / 0 = always two streams
  * Errors: PF_EINVAL for an unknown key or a value outside the stated range. */
 typedef enum {
     PF_OPT_FUSED = 0,
@@ -218,7 +223,8 @@ typedef enum {
     PF_OPT_HIDDEN_MFMA_MIN_ELEMS = 3,
     PF_OPT_UP_GRID = 4,
     PF_OPT_MFMA_GRID = 5,
-    PF_OPT_DOWN_SPLIT = 6
+    PF_OPT_DOWN_SPLIT = 6,
+    PF_OPT_LOOKAHEAD_MERGED = 7
 } pf_option;
 pf_status pf_ctx_set_option(pf_ctx *ctx, int key, int value);
 pf_status pf_ctx_get_option(const pf_ctx *ctx, int key, int *value);

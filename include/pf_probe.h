@@ -31,7 +31,9 @@ typedef enum {
                           barrier timed out)                                                */
     PFP_STREAM_COLD = 7, /* PFP_STREAM, but every launch reads another window of a 1 GiB region
                             (four times the last-level cache), so the bytes come from HBM    */
-    PFP_CHASE_COLD = 8   /* PFP_CHASE through a 1 GiB region, one entry per 128-byte line     */
+    PFP_CHASE_COLD = 8,  /* PFP_CHASE through a 1 GiB region, one entry per 128-byte line     */
+    PFP_CLOCK = 9        /* one lane spins 200 us; *extra = shader clock in MHz (cycle counter
+                            against the constant 100 MHz wall clock)                         */
 } pfp_kind;
 
 /* Runs probe `kind` with `grid` workgroups of 256 threads on the current device.

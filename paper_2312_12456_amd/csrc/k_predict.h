@@ -17,6 +17,63 @@ constexpr int kGlueMaxParts = 4;   // FC2 may hand its output over as up to 4 pa
 constexpr int kPredWaves = kPredThreads / kWave;
 
 // ---------------------------------------------------------------------------------------
+// One pass of the stack glue inside a consumer kernel: S strides of NT * 4 elements of
+// v = sign * (x_prev + sum of FC2's partial sums), for B tokens.  glue_issue puts the loads in
+// flight (x and up to kGlueMaxParts partial sums per element, partials added in the fixed
+// order 0 .. ny-1), glue_commit adds them up, accumulates ||v||^2 per token into ss and
+// stores v in the staged-activation layout of dev_util.h (scrap slot for strides past the
+// vector).  The caller reduces ss over the block and applies sqrt(d / ss) to its dot products.
+template <int B, int S>
+struct GluePass {
+    float4 va[S][B], vc[S][B], vp[S][B][kGlueMaxParts - 1];
+};
+
+template <int B, int S, int NT>
+__device__ __forceinline__ void glue_issue(GluePass<B, S> &gp, rsrc_t xr, rsrc_t yr, uint32_t pbytes,
+                                           int ny, int d, int e0)
+{
+    constexpr int step = NT * 4;
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        const int e = e0 + s * step;
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            const uint32_t off = e < d ? (uint32_t)(b * d + e) * 4u : kOobOffset;
+            gp.va[s][b] = ld16_f32(xr, off);
+            gp.vc[s][b] = ld16_f32(yr, off);
+#pragma unroll
+            for (int p = 1; p < kGlueMaxParts; ++p)  // partial sums of FC2, in order
+                gp.vp[s][b][p - 1] = ld16_f32(yr, (e < d && p < ny) ? off + (uint32_t)p * pbytes : kOobOffset);
+        }
+    }
+}
+
+template <int B, int S, int NT>
+__device__ __forceinline__ void glue_commit(const GluePass<B, S> &gp, float *__restrict__ xs, int kpad,
+                                            int b0, int e0, float (&ss)[B])
+{
+    constexpr int step = NT * 4;
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        const int e = e0 + s * step;
+#pragma unroll
+        for (int b = 0; b < B; ++b) {  // strides past the vector hold zeros: scrap slot
+            const float4 a = gp.va[s][b];
+            float4 c = gp.vc[s][b];
+#pragma unroll
+            for (int p = 1; p < kGlueMaxParts; ++p) {
+                const float4 q = gp.vp[s][b][p - 1];
+                c = make_float4(c.x + q.x, c.y + q.y, c.z + q.z, c.w + q.w);
+            }
+            const float4 v = glue_signed(make_float4(a.x + c.x, a.y + c.y, a.z + c.z, a.w + c.w),
+                                         (uint32_t)b0 + (uint32_t)b, (uint32_t)e);
+            ss[b] = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss[b]))));
+            *reinterpret_cast<float4 *>(xs + (e < kpad ? b * kpad + lds_slot(e) : B * kpad)) = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Hidden layer.  grid = ceil(r / 4); wave w of block g owns row 4g + w.
 // With GLUE the input of the layer is formed on the fly from the previous layer's input and
 // FFN output, x = (xp + yp) * sqrt(d) / ||xp + yp||_2 per token (the stack's residual +
@@ -27,21 +84,20 @@ constexpr int kPredWaves = kPredThreads / kWave;
 // (the glue's sign pattern depends on the row).
 // GS = strides of 1024 elements whose glue loads (x and up to 4 partial sums each) a thread
 // issues together: 4 covers d <= 4096 in a single round trip, at 80 registers.
-template <int B, bool GLUE, int GS = (B >= 2 ? 1 : 2)>
-__global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__restrict__ p1,
-                                                              const float *__restrict__ x,
-                                                              const float *__restrict__ yp, int ny,
-                                                              int ypstride,
-                                                              float *__restrict__ x_new,
-                                                              float *__restrict__ t, int d, int r,
-                                                              int b0)
+// The body takes the block's number explicitly (bid) so that a launch can run it in a range of
+// its blocks beside another role; write_x: this block also writes x for the kernels that follow.
+template <int B, bool GLUE, int GS>
+__device__ __forceinline__ void pred_hidden_body(float *xs, float (*ss_w)[B], const int bid, const bool write_x,
+                                                 const __half *__restrict__ p1,
+                                                 const float *__restrict__ x,
+                                                 const float *__restrict__ yp, int ny,
+                                                 int ypstride, float *__restrict__ x_new,
+                                                 float *__restrict__ t, int d, int r, int b0)
 {
-    extern __shared__ float xs[];
-    __shared__ float ss_w[kPredWaves][B];
     constexpr int U = 8;
     const int lane = threadIdx.x & 63, wave = wave_uniform(threadIdx.x >> 6);
     const int nch = (d + kChunk - 1) / kChunk, kpad = nch * kChunk;
-    const int m = blockIdx.x * kPredWaves + wave;
+    const int m = bid * kPredWaves + wave;
     const bool live = m < r;
     const rsrc_t row = row_rsrc(p1, live ? m : 0, d, live);
 
@@ -60,43 +116,14 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
         const uint32_t pbytes = (uint32_t)ypstride * 4u;  // distance between partials
         const rsrc_t yr = make_rsrc(yp, (uint32_t)(ny - 1) * pbytes + (uint32_t)B * (uint32_t)d * 4u);
         for (int e0 = threadIdx.x * 4; e0 < kpad; e0 += step * S) {
-            float4 va[S][B], vc[S][B], vp[S][B][kGlueMaxParts - 1];
-#pragma unroll
-            for (int s = 0; s < S; ++s) {
-                const int e = e0 + s * step;
-#pragma unroll
-                for (int b = 0; b < B; ++b) {
-                    const uint32_t off = e < d ? (uint32_t)(b * d + e) * 4u : kOobOffset;
-                    va[s][b] = ld16_f32(xr, off);
-                    vc[s][b] = ld16_f32(yr, off);
-#pragma unroll
-                    for (int p = 1; p < kGlueMaxParts; ++p)  // partial sums of FC2, in order
-                        vp[s][b][p - 1] = ld16_f32(yr, (e < d && p < ny) ? off + (uint32_t)p * pbytes : kOobOffset);
-                }
-            }
+            GluePass<B, S> gp;
+            glue_issue<B, S, kPredThreads>(gp, xr, yr, pbytes, ny, d, e0);
             // the row's own loads queue up behind the first pass of activations
             if (!issued) {
                 load_group<U>(g, row, 0, lane);
                 issued = true;
             }
-#pragma unroll
-            for (int s = 0; s < S; ++s) {
-                const int e = e0 + s * step;
-#pragma unroll
-                for (int b = 0; b < B; ++b) {  // strides past the vector hold zeros: scrap slot
-                    const float4 a = va[s][b];
-                    float4 c = vc[s][b];
-#pragma unroll
-                    for (int p = 1; p < kGlueMaxParts; ++p) {
-                        const float4 q = vp[s][b][p - 1];
-                        c = make_float4(c.x + q.x, c.y + q.y, c.z + q.z, c.w + q.w);
-                    }
-                    const float4 v = glue_signed(make_float4(a.x + c.x, a.y + c.y, a.z + c.z, a.w + c.w),
-                                                 (uint32_t)b0 + (uint32_t)b, (uint32_t)e);
-                    ss[b] = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss[b]))));
-                    *reinterpret_cast<float4 *>(xs + (e < kpad ? b * kpad + lds_slot(e) : B * kpad)) = v;
-                }
-            }
+            glue_commit<B, S, kPredThreads>(gp, xs, kpad, b0, e0, ss);
         }
         if (!issued) load_group<U>(g, row, 0, lane);  // threads past a short vector
 #pragma unroll
@@ -112,7 +139,7 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
             for (int k = 0; k < kPredWaves; ++k) tot += ss_w[k][b];
             scale[b] = tot > 0.f ? sqrtf((float)d / tot) : 0.f;
         }
-        if (blockIdx.x == 0) {
+        if (write_x) {
             for (int e = threadIdx.x * 4; e < d; e += kPredThreads * 4) {
 #pragma unroll
                 for (int b = 0; b < B; ++b) {
@@ -146,6 +173,21 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
     PF_TSTAMP(0, 2);
 }
 
+template <int B, bool GLUE, int GS = (B >= 2 ? 1 : 2)>
+__global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__restrict__ p1,
+                                                              const float *__restrict__ x,
+                                                              const float *__restrict__ yp, int ny,
+                                                              int ypstride,
+                                                              float *__restrict__ x_new,
+                                                              float *__restrict__ t, int d, int r,
+                                                              int b0)
+{
+    extern __shared__ float xs[];
+    __shared__ float ss_w[kPredWaves][B];
+    pred_hidden_body<B, GLUE, GS>(xs, ss_w, (int)blockIdx.x, blockIdx.x == 0, p1, x, yp, ny, ypstride,
+                                  x_new, t, d, r, b0);
+}
+
 // ---------------------------------------------------------------------------------------
 // Output layer + threshold + ballot.  grid = ffn / NB; block g owns the NB neurons from
 // NB*g on (NB = 16, 32 or 64: a quarter, half or whole mask word), wave w of it rows
@@ -158,19 +200,21 @@ template <int NB> struct MaskPiece { typedef uint64_t type; };
 template <> struct MaskPiece<32> { typedef uint32_t type; };
 template <> struct MaskPiece<16> { typedef uint16_t type; };
 
-template <int B>
-__global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
-    const __half *__restrict__ p2, const float *__restrict__ p_bias, const float *__restrict__ t,
-    int r, int ffn, float thr_logit, float *__restrict__ scores, uint64_t *__restrict__ mask_words)
+// Body for a block of NB neurons (NB * 16 threads: 4 rows per wave); bid = which NB neurons.
+template <int B, int NB>
+__device__ __forceinline__ void pred_out_body(float *ts, float (*logit_s)[NB], const int bid,
+                                              const __half *__restrict__ p2,
+                                              const float *__restrict__ p_bias,
+                                              const float *__restrict__ t, int r, int ffn,
+                                              float thr_logit, float *__restrict__ scores,
+                                              uint64_t *__restrict__ mask_words)
 {
-    extern __shared__ float ts[];  // [B][kpad] staged hidden vector
-    constexpr int NB = kPredOutNeurons;
-    __shared__ float logit_s[B][NB];
+    constexpr int NT = NB * 16;
     // 16 waves per block leave 128 VGPRs per lane: fewer loads in flight at larger batch
-    constexpr int U = (B <= 2) ? 4 : 2, R = NB / (kPredOutThreads / kWave);
+    constexpr int U = (B <= 2) ? 4 : 2, R = NB / (NT / kWave);
     const int lane = threadIdx.x & 63, wave = wave_uniform(threadIdx.x >> 6);
     const int nch = (r + kChunk - 1) / kChunk, kpad = nch * kChunk;
-    const int n0 = blockIdx.x * NB + wave * R;
+    const int n0 = bid * NB + wave * R;
     rsrc_t rows[R];
 #pragma unroll
     for (int q = 0; q < R; ++q) rows[q] = row_rsrc(p2, n0 + q, r, true);
@@ -211,9 +255,9 @@ __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
     __syncthreads();
 
     if (scores != nullptr) {
-        for (int e = threadIdx.x; e < B * NB; e += kPredOutThreads) {
+        for (int e = threadIdx.x; e < B * NB; e += NT) {
             const int b = e / NB, q = e % NB;
-            scores[(size_t)b * ffn + blockIdx.x * NB + q] = 1.f / (1.f + __expf(-logit_s[b][q]));
+            scores[(size_t)b * ffn + bid * NB + q] = 1.f / (1.f + __expf(-logit_s[b][q]));
         }
     }
     if (wave == 0) {
@@ -222,9 +266,20 @@ __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
         for (int b = 0; b < B; ++b) on = on || (lane < NB && logit_s[b][lane % NB] > thr_logit);
         const uint64_t word = __ballot(on);
         typedef typename MaskPiece<NB>::type piece_t;  // little endian: piece g of the words
-        if (lane == 0) reinterpret_cast<piece_t *>(mask_words)[blockIdx.x] = (piece_t)word;
+        if (lane == 0) reinterpret_cast<piece_t *>(mask_words)[bid] = (piece_t)word;
     }
     PF_TSTAMP(1, 2);
+}
+
+template <int B>
+__global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
+    const __half *__restrict__ p2, const float *__restrict__ p_bias, const float *__restrict__ t,
+    int r, int ffn, float thr_logit, float *__restrict__ scores, uint64_t *__restrict__ mask_words)
+{
+    extern __shared__ float ts[];  // [B][kpad] staged hidden vector
+    __shared__ float logit_s[B][kPredOutNeurons];
+    pred_out_body<B, kPredOutNeurons>(ts, logit_s, (int)blockIdx.x, p2, p_bias, t, r, ffn, thr_logit,
+                                      scores, mask_words);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -31,22 +31,27 @@ inline size_t up_mask_lds_bytes(int ffn)
 // consumer, so the layer step needs no separate compaction launch.
 // Gated forms (ACT == 1): h = ReLU(gate . x + bias) * max(up . x, up_floor); up_floor is
 // -infinity for the plain ReLU-gated block and 0 for dReLU (ReLU on both branches).
-template <int B, int ACT, bool FROM_MASK>
-__global__ __launch_bounds__(kUpThreads) void k_up(
+// GLUE (only with FROM_MASK, inside a stack): the layer input is formed in the kernel from the
+// previous layer's input and FC2 partial sums, like the predictor's hidden kernel does, and
+// applied as a scale on the dot products; the block with write_x set stores it for later kernels.
+// The body takes its block number and the number of blocks of its role explicitly, so that a
+// launch can run it in a range of its blocks beside another role.
+template <int B, int ACT, bool FROM_MASK, bool GLUE>
+__device__ __forceinline__ void up_body(
+    float *xs, uint32_t *wave_tot, float (*ss_w)[B], const int bid, const int nblocks, const bool write_x,
     const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
     const float *__restrict__ b_up, const float *__restrict__ x,
     const int32_t *__restrict__ idx_in, const int32_t *__restrict__ count_in,
     const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
-    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor)
+    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor,
+    const float *__restrict__ yp, int ny, int ypstride, float *__restrict__ x_new)
 {
-    extern __shared__ float xs[];
-    __shared__ uint32_t wave_tot[kUpWaves];
     constexpr int U = 8;
     constexpr bool GATED = (ACT == 1);
     const int lane = threadIdx.x & 63;
     const int wave = wave_uniform(threadIdx.x >> 6);
     const int nch = (d + kChunk - 1) / kChunk, kpad = nch * kChunk;
-    const int stride = gridDim.x * kUpWaves;
+    const int stride = nblocks * kUpWaves;
     const int nwords = ffn / 64;
     uint64_t *words_lds = reinterpret_cast<uint64_t *>(xs + (size_t)B * kpad + kStageScrap);
     uint32_t *pre_lds = reinterpret_cast<uint32_t *>(words_lds + nwords);
@@ -57,15 +62,25 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
     // (measured: 3 % of the stack's time at batch 1, more at larger batches).
     constexpr int SS = (B >= 4) ? 1 : 4 / B;
     Staged<B, SS> st;
-    stage_issue<B, SS>(st, x, d);  // in flight during the mask scan; lands before any weight
+    // glue: strides of 1024 elements whose loads are in flight together (all of d <= 4096 at
+    // batch 1, as in the hidden kernel)
+    constexpr int GS = GLUE ? (B >= 2 ? 1 : 4) : 1;
+    GluePass<B, GS> gp;
+    const rsrc_t xr = make_rsrc(x, (uint32_t)B * (uint32_t)d * 4u);
+    const uint32_t pbytes = (uint32_t)ypstride * 4u;
+    const rsrc_t yr = make_rsrc(yp, GLUE ? (uint32_t)(ny - 1) * pbytes + (uint32_t)B * (uint32_t)d * 4u : 0u);
+    if (GLUE)
+        glue_issue<B, GS, kUpThreads>(gp, xr, yr, pbytes, ny, d, threadIdx.x * 4);
+    else
+        stage_issue<B, SS>(st, x, d);  // in flight during the mask scan; lands before any weight
     int n;
     if (FROM_MASK) {
         n = (int)mask_prefix<kUpThreads>(mask_words, nwords, words_lds, pre_lds, wave_tot);
-        if (blockIdx.x == 0 && threadIdx.x == 0) *count_out = n;
+        if (bid == 0 && threadIdx.x == 0) *count_out = n;
     } else {
         n = min(max(*count_in, 0), ffn);
     }
-    if ((int)blockIdx.x * kUpWaves >= n) return;  // uniform over the block
+    if (bid * kUpWaves >= n && !(GLUE && write_x)) return;  // uniform over the block
     PF_TSTAMP(2, 1);
 
     auto neuron_of = [&](int j) -> int {
@@ -77,7 +92,7 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
         return idx_in[j];
     };
 
-    int j = blockIdx.x * kUpWaves + wave;
+    int j = bid * kUpWaves + wave;
     int i = 0;
     bool valid = false;
     if (j < n) {
@@ -92,8 +107,45 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
     if (GATED) load_group<U>(gg, rg, 0, lane);
 
     PF_TSTAMP(2, 2);
-    stage_commit<B, SS>(st, xs, x, d, kpad);
-    __syncthreads();
+    float scale[B];
+    if (GLUE) {
+        float ss[B];
+#pragma unroll
+        for (int b = 0; b < B; ++b) ss[b] = 0.f;
+        glue_commit<B, GS, kUpThreads>(gp, xs, kpad, 0, threadIdx.x * 4, ss);
+        for (int e0 = threadIdx.x * 4 + kUpThreads * 4 * GS; e0 < kpad; e0 += kUpThreads * 4 * GS) {
+            glue_issue<B, GS, kUpThreads>(gp, xr, yr, pbytes, ny, d, e0);
+            glue_commit<B, GS, kUpThreads>(gp, xs, kpad, 0, e0, ss);
+        }
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            const float s = wave_sum(ss[b]);
+            if (lane == 0) ss_w[wave][b] = s;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            float tot = 0.f;
+#pragma unroll
+            for (int k = 0; k < kUpWaves; ++k) tot += ss_w[k][b];
+            scale[b] = tot > 0.f ? sqrtf((float)d / tot) : 0.f;
+        }
+        if (write_x) {
+            for (int e = threadIdx.x * 4; e < d; e += kUpThreads * 4) {
+#pragma unroll
+                for (int b = 0; b < B; ++b) {
+                    const float4 v = *reinterpret_cast<const float4 *>(xs + b * kpad + lds_slot(e));
+                    *reinterpret_cast<float4 *>(x_new + (size_t)b * d + e) =
+                        make_float4(v.x * scale[b], v.y * scale[b], v.z * scale[b], v.w * scale[b]);
+                }
+            }
+        }
+    } else {
+        stage_commit<B, SS>(st, xs, x, d, kpad);
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < B; ++b) scale[b] = 1.f;
+    }
     PF_TSTAMP(2, 3);
 
     while (j < n) {  // wave-uniform; no block-level synchronisation inside
@@ -125,16 +177,31 @@ __global__ __launch_bounds__(kUpThreads) void k_up(
         for (int b = 0; b < B; ++b) {
             float v;
             if (GATED) {
-                const float gsum = wave_sum(ag[b]) + bias;
-                const float usum = wave_sum(au[b]);
+                const float gsum = (GLUE ? wave_sum(ag[b]) * scale[b] : wave_sum(ag[b])) + bias;
+                const float usum = GLUE ? wave_sum(au[b]) * scale[b] : wave_sum(au[b]);
                 v = fmaxf(gsum, 0.f) * fmaxf(usum, up_floor);
             } else {
-                v = fmaxf(wave_sum(au[b]) + bias, 0.f);
+                v = fmaxf((GLUE ? wave_sum(au[b]) * scale[b] : wave_sum(au[b])) + bias, 0.f);
             }
             if (lane == 0) h[(size_t)jcur * hs + b] = vcur ? v : 0.f;
         }
     }
     PF_TSTAMP(2, 4);
+}
+
+template <int B, int ACT, bool FROM_MASK>
+__global__ __launch_bounds__(kUpThreads) void k_up(
+    const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
+    const float *__restrict__ b_up, const float *__restrict__ x,
+    const int32_t *__restrict__ idx_in, const int32_t *__restrict__ count_in,
+    const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
+    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor)
+{
+    extern __shared__ float xs[];
+    __shared__ uint32_t wave_tot[kUpWaves];
+    up_body<B, ACT, FROM_MASK, false>(xs, wave_tot, nullptr, (int)blockIdx.x, (int)gridDim.x, false, w_up,
+                                      w_gate, b_up, x, idx_in, count_in, mask_words, idx_out, count_out,
+                                      h, hs, d, ffn, up_floor, nullptr, 1, 0, nullptr);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -157,14 +224,13 @@ constexpr int kDown2RowsPerLoad = kDown2Threads / 8;
 constexpr int kDown2MaxSplit = 4;
 
 template <int B>
-__global__ __launch_bounds__(kDown2Threads) void k_down2(
+__device__ __forceinline__ void down2_body(
+    float (*red)[B][kDown2Cols], const int tile, const int g, const int P,
     const __half *__restrict__ w_down, const float *__restrict__ b_down,
     const float *__restrict__ h, const int32_t *__restrict__ idx,
     const int32_t *__restrict__ count_p, float *__restrict__ part, int d, int ffn)
 {
     constexpr int U = (B <= 2) ? 8 : 4;
-    __shared__ float red[kDown2Waves][B][kDown2Cols];
-    const int P = gridDim.y, g = blockIdx.y, tile = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cl = lane & 7;                      // which 16 bytes of the row's 128-byte line
     const int rslot = wave * 8 + (lane >> 3);     // row slot of this lane inside a load
@@ -254,6 +320,17 @@ __global__ __launch_bounds__(kDown2Threads) void k_down2(
         }
     }
     PF_TSTAMP(3, 5);
+}
+
+template <int B>
+__global__ __launch_bounds__(kDown2Threads) void k_down2(
+    const __half *__restrict__ w_down, const float *__restrict__ b_down,
+    const float *__restrict__ h, const int32_t *__restrict__ idx,
+    const int32_t *__restrict__ count_p, float *__restrict__ part, int d, int ffn)
+{
+    __shared__ float red[kDown2Waves][B][kDown2Cols];
+    down2_body<B>(red, (int)blockIdx.x, (int)blockIdx.y, (int)gridDim.y, w_down, b_down, h, idx, count_p,
+                  part, d, ffn);
 }
 
 // y[b][c] = sum of the P partials in order (for callers that need FC2's output itself).

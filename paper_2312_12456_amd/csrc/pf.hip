@@ -19,6 +19,7 @@
 #include "k_int4.h"
 #include "k_mfma.h"
 #include "k_fused.h"
+#include "k_lookahead.h"
 
 namespace {
 
@@ -30,11 +31,12 @@ constexpr int kLdsDefault = 64 * 1024;  // what a kernel may use without opting 
 
 enum KernelId {
     K_PRED_HIDDEN = 0, K_PRED_OUT, K_COMPACT, K_UP, K_DOWN, K_GLUE, K_UP_MFMA, K_COMBINE, K_OUT_UP,
-    K_DOWN_MASK, K_NUM
+    K_DOWN_MASK, K_LA_UP_HIDDEN, K_LA_DOWN_OUT, K_NUM
 };
 const char *const kKernelNames[K_NUM] = {"k_pred_hidden", "k_pred_out", "k_compact", "k_up",
                                          "k_down",        "k_glue",     "k_up_mfma",  "k_combine",
-                                         "k_out_up",      "k_down_mask"};
+                                         "k_out_up",      "k_down_mask", "k_la_up_hidden",
+                                         "k_la_down_out"};
 
 }  // namespace
 
@@ -56,6 +58,8 @@ struct pf_ctx {
     int fused = 1;                 // PF_OPT_FUSED: inner layers of a stack as three launches (0 never,
                                    // 1 where measured faster, 2 wherever possible)
     int seg_strided = 0;           // PF_OPT_SEG_STRIDED: strided segments (models stored hot-first)
+    int la_merged = 1;             // PF_OPT_LOOKAHEAD_MERGED: look-ahead in two launches per layer
+
     uint64_t *mask_trace = nullptr;  // caller's buffer for every layer's mask words (or null)
     int mask_trace_layers = 0;
     // scratch (device)
@@ -183,6 +187,11 @@ hipError_t allow_lds_for_batch()
     if constexpr (B <= 3) {
         if (e == hipSuccess) e = allow_lds(pf::k_out_up<B, 0>);
         if (e == hipSuccess) e = allow_lds(pf::k_out_up<B, 1>);
+        if (e == hipSuccess) e = allow_lds(pf::k_la_up_hidden<B, 0, false>);
+        if (e == hipSuccess) e = allow_lds(pf::k_la_up_hidden<B, 0, true>);
+        if (e == hipSuccess) e = allow_lds(pf::k_la_up_hidden<B, 1, false>);
+        if (e == hipSuccess) e = allow_lds(pf::k_la_up_hidden<B, 1, true>);
+        if (e == hipSuccess) e = allow_lds(pf::k_la_down_out<B>);
     }
     return e;
 }
@@ -686,10 +695,105 @@ pf_status stack_enqueue_lookahead(pf_ctx *ctx, pf_layer *const *layers, int n_la
     return launch_glue(ctx, cur, ctx->ypart, ny, d, B, x_out, st);
 }
 
+// Whether a stack can run look-ahead prediction in the two-launch form (k_lookahead.h): fp16
+// weights and the vector path (batch below the matrix-core kernels', at most 3), whole batch
+// staged at once.
+bool la_merged_ok(const pf_ctx *ctx, pf_layer *const *layers, int n_layers, int B)
+{
+    if (B > 3) return false;
+    for (int l = 0; l < n_layers; ++l) {
+        const pf_layer_desc &D = layers[l]->desc;
+        if (D.wtype != PF_W_FP16 || B >= mfma_from(ctx, D)) return false;
+        if (batch_tile(ctx, D.d, B, pf::up_mask_lds_bytes(D.ffn) + 1024) < B) return false;
+    }
+    return true;
+}
+
+// One decode step with look-ahead prediction, two launches per layer: [hidden layer of
+// predictor l+1 | FC1 of layer l], then [FC2 of layer l | output layer of predictor l+1].
+// The glue runs inside the first launch of the next layer; masks alternate between two buffers.
+pf_status stack_enqueue_lookahead_merged(pf_ctx *ctx, pf_layer *const *layers, int n_layers,
+                                         const float *x, int B, float *x_out, hipStream_t st)
+{
+    uint64_t *masks[2] = {ctx->mask_words, ctx->mask_words2};
+    const int d = layers[0]->desc.d;
+    // the list of layer 0 comes from its own input
+    pf_status s = launch_predict(ctx, layers[0], x, nullptr, 0, nullptr, B, nullptr, masks[0], st);
+    if (s != PF_OK) return s;
+    int ny = 1;
+    const float *cur = x;  // what the first launch of layer l reads: x_0, or the input of layer l-1
+    for (int l = 0; l < n_layers; ++l) {
+        const pf_layer *L = layers[l];
+        const pf_layer *N = l + 1 < n_layers ? layers[l + 1] : nullptr;  // whose predictor rides along
+        const pf_layer_desc &D = L->desc;
+        const bool gated = D.act != PF_ACT_RELU;
+        const bool glue = l > 0;
+        float *xn = glue ? ctx->xbuf[l & 1] : nullptr;
+        const int n_hid = N ? cdiv(N->desc.r, pf::kPredWaves) : 0;
+        int n_up = cdiv(D.ffn, pf::kUpWaves);
+        // Measured on the benchmark shapes (batch 1..3): the roles with the dependent chains
+        // (FC1, FC2) take the low block numbers, FC1 gets two workgroups per CU (every one of
+        // them forms the glue, so surplus workgroups cost cache reads), and FC2 leaves two
+        // partial sums instead of four (fewer CUs gather, but the output layer's stream keeps
+        // the others busy, and the next launch reads 3 instead of 5 vectors per workgroup).
+        if (n_up > 2 * ctx->num_cu) n_up = 2 * ctx->num_cu;
+        const size_t lds1 = ((size_t)B * kpad_of(D.d) + pf::kStageScrap) * sizeof(float) +
+                            pf::up_mask_lds_bytes(D.ffn);
+        {
+            ProfScope ps(ctx, K_LA_UP_HIDDEN);
+#define PF_LA1(ACT, GLUE)                                                                          \
+    PF_SWITCH_B3(B, PF_LAUNCH(ps, (pf::k_la_up_hidden<BT, ACT, GLUE>), dim3(n_hid + n_up),          \
+                              dim3(pf::kUpThreads), lds1, st, n_hid,                                \
+                              static_cast<const __half *>(N ? N->w.p1 : nullptr), ctx->t,           \
+                              N ? N->desc.r : 0, static_cast<const __half *>(L->w.w_up),            \
+                              static_cast<const __half *>(L->w.w_gate), L->w.b_up, cur,             \
+                              (const float *)ctx->ypart, ny, B * d, xn,                             \
+                              (const uint64_t *)masks[l & 1], ctx->idx, ctx->count, ctx->h,         \
+                              pf::h_stride(B), D.d, D.ffn, up_floor_of(D), true))
+            if (gated && glue) { PF_LA1(1, true); }
+            else if (gated) { PF_LA1(1, false); }
+            else if (glue) { PF_LA1(0, true); }
+            else { PF_LA1(0, false); }
+#undef PF_LA1
+        }
+        if (glue) cur = xn;
+        ctx->last_mask = masks[l & 1];
+        ctx->last_idx = ctx->idx;
+        ctx->last_count = ctx->count;
+        const int tiles = cdiv(D.d, pf::kDown2Cols);
+        int P = ctx->down_split > 0 ? ctx->down_split : ctx->num_cu / tiles;
+        if (P < 1) P = 1;
+        if (ctx->down_split == 0 && P > 2) P = 2;
+        if (P > pf::kDown2MaxSplit) P = pf::kDown2MaxSplit;
+        const int n_out = N ? N->desc.ffn / pf::kLaOutNeurons : 0;
+        const size_t lds2 = N ? ((size_t)B * kpad_of(N->desc.r) + pf::kStageScrap) * sizeof(float) : 0;
+        {
+            ProfScope ps(ctx, K_LA_DOWN_OUT);
+            PF_SWITCH_B3(B, PF_LAUNCH(ps, (pf::k_la_down_out<BT>), dim3(tiles * P + n_out),
+                                      dim3(pf::kDown2Threads), lds2, st, tiles, P,
+                                      static_cast<const __half *>(L->w.w_down), L->w.b_down,
+                                      (const float *)ctx->h, (const int32_t *)ctx->idx,
+                                      (const int32_t *)ctx->count, ctx->ypart, D.d, D.ffn,
+                                      static_cast<const __half *>(N ? N->w.p2 : nullptr),
+                                      N ? N->w.p_bias : nullptr, (const float *)ctx->t,
+                                      N ? N->desc.r : 0, N ? N->desc.ffn : 0, N ? N->thr_logit : 0.f,
+                                      masks[(l + 1) & 1], false));
+        }
+        ny = P;
+        PF_HIP(ctx, hipGetLastError());
+        s = trace_mask(ctx, l, L, masks[l & 1], false, st);
+        if (s != PF_OK) return s;
+    }
+    return launch_glue(ctx, cur, ctx->ypart, ny, d, B, x_out, st);
+}
+
 pf_status stack_enqueue(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x, int B,
                         float *x_out, hipStream_t st)
 {
-    if (ctx->lookahead) return stack_enqueue_lookahead(ctx, layers, n_layers, x, B, x_out, st);
+    if (ctx->lookahead)
+        return ctx->la_merged && la_merged_ok(ctx, layers, n_layers, B)
+                   ? stack_enqueue_lookahead_merged(ctx, layers, n_layers, x, B, x_out, st)
+                   : stack_enqueue_lookahead(ctx, layers, n_layers, x, B, x_out, st);
     int ny = 1;            // partial sums FC2 left in ctx->ypart
     const float *cur = x;  // input of the layer being enqueued (raw input of the previous one
                            // until the hidden kernel has formed it)
@@ -1141,6 +1245,11 @@ pf_status pf_ctx_set_option(pf_ctx *ctx, int key, int value)
             if (value < 0 || value > pf::kDown2MaxSplit) break;
             ctx->down_split = value;
             return PF_OK;
+        case PF_OPT_LOOKAHEAD_MERGED:
+            if (value < 0 || value > 1) break;
+            ctx->la_merged = value;
+            return PF_OK;
+
         default:
             return fail(ctx, PF_EINVAL, "unknown option %d", key);
     }
@@ -1158,6 +1267,7 @@ pf_status pf_ctx_get_option(const pf_ctx *ctx, int key, int *value)
         case PF_OPT_UP_GRID: *value = ctx->up_grid_cap; break;
         case PF_OPT_MFMA_GRID: *value = ctx->mfma_grid; break;
         case PF_OPT_DOWN_SPLIT: *value = ctx->down_split; break;
+        case PF_OPT_LOOKAHEAD_MERGED: *value = ctx->la_merged; break;
         default: return PF_EINVAL;
     }
     return PF_OK;

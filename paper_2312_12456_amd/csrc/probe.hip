@@ -78,6 +78,17 @@ __global__ __launch_bounds__(256) void k_stream(const void *__restrict__ src, ui
     if (acc == 0x9e3779b9u) *sink = 1;
 }
 
+// shader clock: cycle counter against the constant 100 MHz wall clock over a fixed spin
+__global__ void k_clock(unsigned long long *out)
+{
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    const unsigned long long w0 = wall_clock64(), c0 = clock64();
+    unsigned long long w1 = w0;
+    while (w1 - w0 < 20000ull) w1 = wall_clock64();  // 200 us; ends whatever the clocks do
+    out[0] = clock64() - c0;
+    out[1] = w1 - w0;
+}
+
 __global__ void k_fill(uint32_t *p, int n, uint32_t v)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -284,6 +295,7 @@ int pfp_measure(int kind, size_t bytes, int grid, int nodes, int reps, double *g
                 PFP_L(k_stream, (const void *)win, (uint32_t)B.big_bytes, B.b);
                 break;
             }
+            case PFP_CLOCK: PFP_L(k_clock, B.ticks); break;
             case PFP_CHASE_COLD:
                 PFP_L(k_chase_cold, (const int *)B.big, (int)(bytes ? bytes : 64), (i * 7919) & 0xfffff, B.b);
                 break;
@@ -291,7 +303,7 @@ int pfp_measure(int kind, size_t bytes, int grid, int nodes, int reps, double *g
         }
 #undef PFP_L
     };
-    if (kind < 0 || kind > PFP_CHASE_COLD) {
+    if (kind < 0 || kind > PFP_CLOCK) {
         snprintf(g_err, sizeof(g_err), "unknown probe %d", kind);
         return 1;
     }
@@ -330,6 +342,11 @@ int pfp_measure(int kind, size_t bytes, int grid, int nodes, int reps, double *g
             unsigned long long t = 0;
             PFP_HIP(hipMemcpy(&t, B.ticks, 8, hipMemcpyDeviceToHost));
             *extra = nb > 0 ? (double)t / 100.0 / nb : 0.0;  // 100 MHz clock -> us per barrier
+        }
+        if (kind == PFP_CLOCK) {
+            unsigned long long t[2] = {0, 0};
+            PFP_HIP(hipMemcpy(t, B.ticks, 16, hipMemcpyDeviceToHost));
+            *extra = t[1] ? (double)t[0] / ((double)t[1] / 100.0) : 0.0;  // cycles per us = MHz
         }
         if (kind == PFP_EXCHANGE) {
             uint32_t m = 0, err = 0;

@@ -7,7 +7,7 @@ import torch
 
 from paper_2312_12456_amd import workload as wl
 from tests.util import (MaskTrace, check_active_set, check_output, oracle_chain_on_device_sets,
-                        oracle_layer)
+                        oracle_layer, oracle_lookahead_chain_on_device_sets)
 
 pytestmark = pytest.mark.gpu
 
@@ -139,3 +139,36 @@ def test_full_shape_stack_three_launch_form_matches_oracle(pf, oracle, name, B):
     assert n_cmp == cfg.layers
     assert in_band < 0.005 * cfg.ffn * B * cfg.layers + 16
     check_output(out.cpu().numpy(), ref, name + " three-launch stack")
+
+
+@pytest.mark.parametrize("name,B", [("opt-6.7b", 1), ("opt-6.7b", 3), ("llama2-13b-reglu", 2), ("opt-30b", 2)])
+def test_full_shape_lookahead_two_launch_form_matches_oracle(pf, oracle, name, B):
+    """Three full-size layers with look-ahead prediction through the recorded plan, in the form
+    with two launches per layer (next layer's predictor beside this layer's sparse kernels):
+    every layer's set against the oracle's look-ahead rule outside the score band, the output
+    against the oracle's stack run on those sets."""
+    cfg = wl.scaled(wl.CONFIGS[name], layers=3)
+    ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
+    ctx.set_lookahead(1)
+    lays = [wl.make_layer(cfg, l, seed=2312, device="cuda") for l in range(cfg.layers)]
+    Ls = [pf.Layer.from_workload(ctx, cfg, t) for t in lays]
+    x0 = wl.make_inputs(cfg, 2, seed=2312, batch=B, device="cuda")
+    trace = MaskTrace(ctx, cfg.layers, cfg.ffn)
+    out = torch.full_like(x0, float("nan"))
+    plan = pf.Plan(ctx, Ls, x0, out)
+    plan.run()
+    torch.cuda.synchronize()
+    plan.close()
+    eager = torch.empty_like(x0)
+    ctx.profile_begin()
+    ctx.stack_step(Ls, x0, eager)
+    stats = ctx.profile_end()
+    ctx.set_mask_trace(None)
+    assert stats["k_la_up_hidden"][0] == 3 and stats["k_la_down_out"][0] == 3, stats
+    assert torch.equal(eager, out)
+    Os = [oracle_layer(cfg, wl.to_host(t)) for t in lays]
+    ref, n_cmp, in_band = oracle_lookahead_chain_on_device_sets(
+        oracle, Os, x0.cpu().numpy(), trace.masks(), cfg.threshold, name)
+    assert n_cmp == cfg.layers
+    assert in_band < 0.005 * cfg.ffn * B * cfg.layers + 16
+    check_output(out.cpu().numpy(), ref, name + " look-ahead stack")

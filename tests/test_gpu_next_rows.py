@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2312_12456_amd import workload as wl
-from tests.util import check_output, oracle_layer, small_cfg
+from tests.util import MaskTrace, check_output, oracle_layer, small_cfg
 
 pytestmark = pytest.mark.gpu
 
@@ -106,13 +106,16 @@ def test_count_activations_equals_oracle_counts(pf):
     assert np.array_equal(counts.cpu().numpy(), got + 1)
 
 
-@pytest.mark.parametrize("B", [1, 4])
-@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
+@pytest.mark.parametrize("B", [1, 2, 3, 4])
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU, wl.ACT_DRELU])
 def test_stack_lookahead_matches_oracle(pf, act, B):
-    """Look-ahead prediction at distance 1 through pf_stack_step and a recorded plan (two
-    streams inside the library) against the oracle's look-ahead stack: final output within the
-    output bar, last layer's list bit exact.  A seed is used only if no oracle score of any
-    layer lies within 1e-4 of the threshold, so that no decision can differ by rounding."""
+    """Look-ahead prediction at distance 1 through pf_stack_step and a recorded plan against the
+    oracle's look-ahead stack, in both forms the library has: two launches per layer whose block
+    ranges run the next layer's predictor beside this layer's sparse kernels (fp16, batch <= 3),
+    and predictors on a second stream.  Every layer's active set bit exact (read through the
+    mask trace), final output within the output bar, last layer's list bit exact.  A seed is
+    used only if no oracle score of any layer lies within 1e-4 of the threshold, so that no
+    decision can differ by rounding."""
     from oracle import pf_oracle
     n_layers = 4
     cfg = small_cfg(d=520, ffn=1344, r=136, act=act, rate=0.1, layers=n_layers)
@@ -139,23 +142,39 @@ def test_stack_lookahead_matches_oracle(pf, act, B):
     ctx.stack_step(Ls, x, plain)
     torch.cuda.synchronize()
     ctx.set_lookahead(1)
-    out = torch.full_like(x, float("nan"))
-    ctx.stack_step(Ls, x, out)
-    torch.cuda.synchronize()
-    check_output(out.cpu().numpy(), ref, "look-ahead stack")
-    assert not torch.allclose(out, plain, atol=1e-3)
-    _, lst = _last_list(pf, ctx, cfg.ffn)
-    assert np.array_equal(lst, np.flatnonzero(masks[-1]))
-    # ... and the recorded plan replays it
-    out2 = torch.zeros_like(x)
-    plan = pf.Plan(ctx, Ls, x, out2)
-    for _ in range(3):
-        out2.zero_()
-        plan.run()
+    trace = MaskTrace(ctx, n_layers, cfg.ffn)
+    outs = {}
+    for merged in (1, 0):
+        ctx.set_option(pf.OPT_LOOKAHEAD_MERGED, merged)
+        out = torch.full_like(x, float("nan"))
+        trace.buf.fill_(-1)
+        ctx.profile_begin()
+        ctx.stack_step(Ls, x, out)
+        stats = ctx.profile_end()
         torch.cuda.synchronize()
-        assert torch.equal(out2, out)
-        _ = (x + 1).sum().item()
-    plan.close()
+        two_launch = merged == 1 and B <= 3
+        assert stats["k_la_up_hidden"][0] == (n_layers if two_launch else 0), stats
+        assert stats["k_la_down_out"][0] == (n_layers if two_launch else 0), stats
+        check_output(out.cpu().numpy(), ref, "look-ahead stack (merged=%d)" % merged)
+        for l, m in enumerate(trace.masks()):
+            assert np.array_equal(m, masks[l]), "layer %d set differs (merged=%d)" % (l, merged)
+        assert not torch.allclose(out, plain, atol=1e-3)
+        _, lst = _last_list(pf, ctx, cfg.ffn)
+        assert np.array_equal(lst, np.flatnonzero(masks[-1]))
+        # ... and the recorded plan replays it
+        out2 = torch.zeros_like(x)
+        plan = pf.Plan(ctx, Ls, x, out2)
+        for _ in range(3):
+            out2.zero_()
+            plan.run()
+            torch.cuda.synchronize()
+            assert torch.equal(out2, out)
+            _ = (x + 1).sum().item()
+        plan.close()
+        outs[merged] = out
+    # the two forms run the same arithmetic per neuron; FC2's sum has the same order
+    np.testing.assert_allclose(outs[1].cpu().numpy(), outs[0].cpu().numpy(), atol=2e-4, rtol=0)
+    ctx.set_mask_trace(None)
     ctx.set_lookahead(0)
     again = torch.empty_like(x)
     ctx.stack_step(Ls, x, again)

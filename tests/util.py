@@ -89,3 +89,16 @@ def oracle_chain_on_device_sets(oracle_mod, Os, x0, masks, threshold, what=""):
         in_band += check_active_set(m, sc, threshold, "%s layer %d" % (what, l))
         xo = oracle_mod.stack_glue(xo, O.masked_ffn(xo, m))
     return xo, len(masks), in_band
+
+
+def oracle_lookahead_chain_on_device_sets(oracle_mod, Os, x0, masks, threshold, what=""):
+    """The same for look-ahead prediction at distance 1: the set of layer l is checked against
+    layer l's predictor applied to the oracle's input of layer l - 1 (layer 0: its own input)."""
+    xo = np.asarray(x0, dtype=np.float32)
+    inputs, in_band = [], 0
+    for l, (O, m) in enumerate(zip(Os, masks)):
+        inputs.append(xo)
+        seen = inputs[0] if l == 0 else inputs[l - 1]
+        in_band += check_active_set(m, O.predict(seen)["scores"], threshold, "%s layer %d" % (what, l))
+        xo = oracle_mod.stack_glue(xo, O.masked_ffn(xo, m))
+    return xo, len(masks), in_band
