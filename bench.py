@@ -250,11 +250,21 @@ def main():
                 ctx.count_activations(L, tabs[l])
                 ctx.stack_glue(xa0, y0, xa0)
         torch.cuda.synchronize()
+        n_prof = min(args.sort_neurons, n_tok)
+        tables, prefix = [], []
         for l in range(cfg.layers):
-            order = torch.argsort(tabs[l], descending=True, stable=True).cpu().numpy()
-            tensors[l] = wl.permute_neurons(tensors[l], order)
+            order_t = torch.argsort(tabs[l], descending=True, stable=True)
+            # neurons listed in at least 90 % of the profiled tokens form the always-on prefix:
+            # the library lists them without evaluating their predictor rows
+            hot = int((tabs[l] >= 0.9 * n_prof).sum().item())
+            a_on = min(64 * (hot // 64), cfg.ffn - 64)
+            tensors[l] = wl.permute_neurons(tensors[l], order_t.cpu().numpy())
             layers[l] = pf.Layer.from_workload(ctx, cfg, tensors[l])
+            tables.append(order_t.to(torch.int32).contiguous())
+            layers[l].set_neuron_table(tables[l], a_on)
+            prefix.append(a_on)
         torch.cuda.synchronize()
+        sort_info = {"profiled_tokens": n_prof, "always_on_mean": float(np.mean(prefix))}
 
     ctx.set_lookahead(args.lookahead)
     plan = pf.Plan(ctx, layers, x_buf, out) if args.mode == "graph" else None
@@ -473,7 +483,9 @@ def main():
                                   B, cfg.alpha, 100 * cfg.rate, K),
                    "launch": args.mode, "predictor_bias": not args.no_pred_bias,
                    "lookahead": args.lookahead,
-                   "neuron_layout": ("hot-first from %d profiled tokens" % args.sort_neurons)
+                   "neuron_layout": ("hot-first from %d profiled tokens through the library's neuron "
+                                     "table, always-on prefix of %.0f neurons per layer on average"
+                                     % (sort_info["profiled_tokens"], sort_info["always_on_mean"]))
                    if args.sort_neurons > 0 else "as generated"},
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -173,11 +173,31 @@ pf_status pf_layer_step_auto(pf_ctx *ctx, const pf_layer *layer, const float *x,
                              float density_hint, float crossover, float *y, void *stream);
 
 /* Activation profiler (the counting of Sec. 6.1 that fills the neuron table): counts[i] += 1
- * for every neuron i of the list the context used last (pf_layer_step, pf_layer_step_auto,
+ * for every neuron i -- in the model's numbering when the layer has a neuron table -- of the
+ * list the context used last (pf_layer_step, pf_layer_step_auto,
  * pf_dense_ffn; not pf_sparse_ffn, whose list is the caller's).  counts: [ffn] uint32 on the
  * device, caller-owned, zeroed by the caller before the first call.  One launch on `stream`,
  * no host synchronisation; the list holds no duplicates, so no atomics are involved. */
 pf_status pf_count_activations(pf_ctx *ctx, const pf_layer *layer, uint32_t *counts, void *stream);
+
+/* Neuron table of a layer (Sec. 5.2 neuron tables, Sec. 6.1 offline profiling): the weights
+ * handed to pf_layer_create may be stored in another neuron order than the model's -- hot-first
+ * from a profile, which is what a sort by activation frequency (Eq. 1 on a single memory tier)
+ * gives.  stored_to_original: device array [ffn], a permutation, entry j = the model's number
+ * of the neuron stored at position j; borrowed until pf_layer_destroy; NULL = identity.
+ * always_on: the first always_on stored neurons (a multiple of 64, at most ffn - 64) are
+ * treated as active in every step WITHOUT being predicted: the predictor's output layer
+ * skips their rows (2 r bytes each) and their mask bits and scores read 1.  All internal lists
+ * and masks (pf_predict, pf_ctx_last_active, the mask trace) stay in stored numbering;
+ * pf_layer_active_original and pf_count_activations translate through the table. */
+pf_status pf_layer_set_neuron_table(pf_layer *layer, const int32_t *stored_to_original, int always_on);
+
+/* The active set the context used last (as pf_ctx_last_active), in the MODEL's neuron numbering:
+ * mask_words [ffn/64] uint64 (bit b of word w = original neuron 64 w + b), idx [ffn capacity]
+ * int32 ascending original numbers, *count their number; all device, caller-owned, fully
+ * overwritten.  Three small launches on `stream`, no host synchronisation. */
+pf_status pf_layer_active_original(pf_ctx *ctx, const pf_layer *layer, uint64_t *mask_words,
+                                   int32_t *idx, int32_t *count, void *stream);
 
 /* Device pointers to the mask words, index list and count left by the last layer step on
  * this context (valid until the next compute call).  After a dense step idx / count are the

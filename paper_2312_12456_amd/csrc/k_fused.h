@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kPredOutThreads) void k_out_up(
     const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
     const float *__restrict__ b_up, const float *__restrict__ x, int r, int d, int ffn, int hs,
     float thr_logit, bool strided, uint64_t *__restrict__ seg_words,
-    uint8_t *__restrict__ seg_pos, float *__restrict__ h, float up_floor)
+    uint8_t *__restrict__ seg_pos, float *__restrict__ h, float up_floor, int always_on)
 {
     extern __shared__ float ts[];  // [B][rpad] hidden vector, then [B][dpad] layer input
     static_assert(kPredOutNeurons == 64, "one mask word per block");
@@ -72,9 +72,18 @@ __global__ __launch_bounds__(kPredOutThreads) void k_out_up(
     const int G = gridDim.x, g0 = blockIdx.x;
     rsrc_t rows[R];
 #pragma unroll
-    for (int q = 0; q < R; ++q) rows[q] = row_rsrc(p2, seg_neuron(wave * R + q, g0, G, strided), r, true);
+    for (int q = 0; q < R; ++q) {  // neurons below always_on are taken without reading their rows
+        const int nq = seg_neuron(wave * R + q, g0, G, strided);
+        rows[q] = row_rsrc(p2, nq, r, nq >= always_on);
+    }
 
     PF_TSTAMP(4, 0);
+    // a segment of the always-on prefix: no predictor rows are read, every neuron is taken
+    const bool all_on = !strided && g0 * 64 + 63 < always_on;  // uniform over the block
+    if (all_on) {
+        stage_dma<B>(xs, x, d, dpad);
+        __syncthreads();
+    } else {
     stage_dma<B>(ts, t, r, rpad);
     constexpr int PRE = 2;  // rows whose loads are issued before the block barrier
     WGroup<UP> g[R];
@@ -112,11 +121,14 @@ __global__ __launch_bounds__(kPredOutThreads) void k_out_up(
         }
     }
     __syncthreads();
+    }
     PF_TSTAMP(4, 2);
 
-    bool on = false;
+    bool on = seg_neuron(lane, g0, G, strided) < always_on;
+    if (!all_on) {
 #pragma unroll
-    for (int b = 0; b < B; ++b) on = on || (logit_s[b][lane] > thr_logit);
+        for (int b = 0; b < B; ++b) on = on || (logit_s[b][lane] > thr_logit);
+    }
     const uint64_t word = __ballot(on);
     const int myrank = __popcll(word & ((1ull << lane) - 1ull));
     if (wave == 0) {

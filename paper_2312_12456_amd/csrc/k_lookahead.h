@@ -61,7 +61,7 @@ __global__ __launch_bounds__(kDown2Threads) void k_la_down_out(
     const float *__restrict__ h, const int32_t *__restrict__ idx, const int32_t *__restrict__ count_p,
     float *__restrict__ part, int d, int ffn, const __half *__restrict__ p2,
     const float *__restrict__ p_bias, const float *__restrict__ t, int r, int ffn_next, float thr_logit,
-    uint64_t *__restrict__ mask_next, bool out_first)
+    uint64_t *__restrict__ mask_next, int first_word, bool out_first)
 {
     extern __shared__ float ts[];
     __shared__ float red[kDown2Waves][B][kDown2Cols];
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kDown2Threads) void k_la_down_out(
         down2_body<B>(red, fb % tiles, fb / tiles, P, w_down, b_down, h, idx, count_p, part, d, ffn);
     } else {
         pred_out_body<B, kLaOutNeurons>(ts, logit_s, out_first ? bid : bid - n_fc2, p2, p_bias, t, r,
-                                        ffn_next, thr_logit, nullptr, mask_next);
+                                        ffn_next, thr_logit, nullptr, mask_next, first_word);
     }
 }
 

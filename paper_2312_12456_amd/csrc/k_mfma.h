@@ -345,7 +345,7 @@ template <int R, int KC, int EPI>
 __global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
     const __half *__restrict__ w, const float *__restrict__ v, int B, int K, int nrows,
     const float *__restrict__ p_bias, float thr_logit, float *__restrict__ out,
-    uint64_t *__restrict__ mask_words)
+    uint64_t *__restrict__ mask_words, int first_word)
 {
     extern __shared__ uint64_t dyn_lds64[];
     constexpr int T = (R + 15) / 16;  // MFMA tiles per block
@@ -358,8 +358,16 @@ __global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
     const int row16 = lane & 15, kg = lane >> 4;
     char *slots = reinterpret_cast<char *>(dyn_lds64);
     char *slot = slots + (size_t)wave * kRowsMfmaSlotBytes;
-    const int r0 = blockIdx.x * R;
+    // EPI 1: the launch covers the rows from 64 * first_word on (always-on prefix skipped)
+    const int blk = (int)blockIdx.x + (EPI == 1 ? first_word : 0);
+    const int r0 = blk * R;
     const int nleft = nrows - r0;  // rows of this block that exist (>= 1)
+    if (EPI == 1 && blockIdx.x == 0 && first_word > 0) {
+        for (int w = threadIdx.x; w < first_word; w += kMfmaThreads) mask_words[w] = ~0ull;
+        if (out != nullptr)
+            for (int e = threadIdx.x; e < B * first_word * 64; e += kMfmaThreads)
+                out[(size_t)(e / (first_word * 64)) * nrows + e % (first_word * 64)] = 1.f;
+    }
     const rsrc_t wr = make_rsrc(w, (uint32_t)nrows * (uint32_t)K * 2u);
     const rsrc_t vr = make_rsrc(v, (uint32_t)B * (uint32_t)K * 4u);
     const uint32_t row_bytes = (uint32_t)K * 2u, row0_off = (uint32_t)r0 * row_bytes;
@@ -460,7 +468,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
             bool on = false;
             for (int b = 0; b < B; ++b) on = on || logit_s[b][lane] > thr_logit;
             const uint64_t word = __ballot(on);
-            if (lane == 0) mask_words[blockIdx.x] = word;
+            if (lane == 0) mask_words[blk] = word;
         }
     }
     PF_TSTAMP(EPI, 2);

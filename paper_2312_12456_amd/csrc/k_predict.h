@@ -189,8 +189,8 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
 }
 
 // ---------------------------------------------------------------------------------------
-// Output layer + threshold + ballot.  grid = ffn / NB; block g owns the NB neurons from
-// NB*g on (NB = 16, 32 or 64: a quarter, half or whole mask word), wave w of it rows
+// Output layer + threshold + ballot.  grid = (ffn - 64 first_word) / NB; block g owns the NB
+// neurons from 64 first_word + NB*g on (NB = 16, 32 or 64: a quarter, half or whole mask word), wave w of it rows
 // 4w .. 4w+3, all in flight at once; wave 0 turns the NB decisions into its piece of the
 // mask word with a ballot.
 constexpr int kPredOutNeurons = 64;
@@ -200,16 +200,32 @@ template <int NB> struct MaskPiece { typedef uint64_t type; };
 template <> struct MaskPiece<32> { typedef uint32_t type; };
 template <> struct MaskPiece<16> { typedef uint16_t type; };
 
+// Writes "always on" for the first `words` mask words (and score 1 for their neurons): the
+// neurons of an always-on prefix are not evaluated by the predictor's output layer at all.
+// Called by one workgroup of the output-layer kernels.
+template <int B>
+__device__ __forceinline__ void mark_always_on(int words, int ffn, float *__restrict__ scores,
+                                               uint64_t *__restrict__ mask_words)
+{
+    for (int w = threadIdx.x; w < words; w += blockDim.x) mask_words[w] = ~0ull;
+    if (scores != nullptr)
+        for (int e = threadIdx.x; e < B * words * 64; e += blockDim.x)
+            scores[(size_t)(e / (words * 64)) * ffn + e % (words * 64)] = 1.f;
+}
+
 // Body for a block of NB neurons (NB * 16 threads: 4 rows per wave); bid = which NB neurons.
+// The launch covers the neurons from 64 * first_word on; its first block marks the words below.
 template <int B, int NB>
-__device__ __forceinline__ void pred_out_body(float *ts, float (*logit_s)[NB], const int bid,
+__device__ __forceinline__ void pred_out_body(float *ts, float (*logit_s)[NB], const int bid0,
                                               const __half *__restrict__ p2,
                                               const float *__restrict__ p_bias,
                                               const float *__restrict__ t, int r, int ffn,
                                               float thr_logit, float *__restrict__ scores,
-                                              uint64_t *__restrict__ mask_words)
+                                              uint64_t *__restrict__ mask_words, const int first_word)
 {
     constexpr int NT = NB * 16;
+    const int bid = bid0 + first_word * (64 / NB);
+    if (bid0 == 0 && first_word > 0) mark_always_on<B>(first_word, ffn, scores, mask_words);
     // 16 waves per block leave 128 VGPRs per lane: fewer loads in flight at larger batch
     constexpr int U = (B <= 2) ? 4 : 2, R = NB / (NT / kWave);
     const int lane = threadIdx.x & 63, wave = wave_uniform(threadIdx.x >> 6);
@@ -274,12 +290,13 @@ __device__ __forceinline__ void pred_out_body(float *ts, float (*logit_s)[NB], c
 template <int B>
 __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
     const __half *__restrict__ p2, const float *__restrict__ p_bias, const float *__restrict__ t,
-    int r, int ffn, float thr_logit, float *__restrict__ scores, uint64_t *__restrict__ mask_words)
+    int r, int ffn, float thr_logit, float *__restrict__ scores, uint64_t *__restrict__ mask_words,
+    int first_word)
 {
     extern __shared__ float ts[];  // [B][kpad] staged hidden vector
     __shared__ float logit_s[B][kPredOutNeurons];
     pred_out_body<B, kPredOutNeurons>(ts, logit_s, (int)blockIdx.x, p2, p_bias, t, r, ffn, thr_logit,
-                                      scores, mask_words);
+                                      scores, mask_words, first_word);
 }
 
 // ---------------------------------------------------------------------------------------

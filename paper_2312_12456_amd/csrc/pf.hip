@@ -93,6 +93,8 @@ struct pf_layer {
     pf_layer_desc desc;
     pf_layer_weights w;
     float thr_logit;
+    const int32_t *table = nullptr;  // stored neuron -> original neuron (borrowed), or null
+    int always_on = 0;               // stored neurons [0, always_on) are listed without prediction
 };
 
 struct pf_plan {
@@ -299,7 +301,7 @@ pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const fl
         ProfScope ps(ctx, K_PRED_HIDDEN);
         PF_LAUNCH(ps, (pf::k_rows_mfma<8, 512, 0>), dim3(cdiv(D.r, 8)), dim3(pf::kMfmaThreads),
                   (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p1, x, B, D.d, D.r,
-                  (const float *)nullptr, 0.f, ctx->t, (uint64_t *)nullptr);
+                  (const float *)nullptr, 0.f, ctx->t, (uint64_t *)nullptr, 0);
         PF_HIP(ctx, hipGetLastError());
         return PF_OK;
     }
@@ -331,6 +333,11 @@ pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const fl
     return PF_OK;
 }
 
+// Workgroups of the predictor's output layer: one per mask word past the always-on prefix; at
+// least one, which then also marks the prefix (a layer whose neurons are all always on keeps
+// its last word predicted).
+inline int pred_out_words(const pf_layer *L) { return L->desc.ffn / 64 - L->always_on / 64; }
+
 // Predictor: hidden layer, then output layer + ballot into mask words.
 pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
                          int glue_ny, float *x_new, int B, float *scores, uint64_t *mask_words,
@@ -342,20 +349,20 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
     const __half *p2 = static_cast<const __half *>(L->w.p2);
     if (pred_mfma(ctx, D, D.r, B)) {
         ProfScope ps(ctx, K_PRED_OUT);
-        PF_LAUNCH(ps, (pf::k_rows_mfma<64, 64, 1>), dim3(D.ffn / 64), dim3(pf::kMfmaThreads),
+        PF_LAUNCH(ps, (pf::k_rows_mfma<64, 64, 1>), dim3(pred_out_words(L)), dim3(pf::kMfmaThreads),
                   (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p2, (const float *)ctx->t, B, D.r,
-                  D.ffn, L->w.p_bias, L->thr_logit, scores, mask_words);
+                  D.ffn, L->w.p_bias, L->thr_logit, scores, mask_words, L->always_on / 64);
         PF_HIP(ctx, hipGetLastError());
         return PF_OK;
     }
     // output layer over the whole batch (its staged vector is only B * r floats)
     const size_t lds = ((size_t)B * kpad_of(D.r) + pf::kStageScrap) * sizeof(float);
-    const dim3 grid(D.ffn / pf::kPredOutNeurons);
+    const dim3 grid(pred_out_words(L));
     {
         ProfScope ps(ctx, K_PRED_OUT);
         PF_SWITCH_B(B, PF_LAUNCH(ps, pf::k_pred_out<BT>, grid, dim3(pf::kPredOutThreads), lds,
                                           st, p2, L->w.p_bias, ctx->t, D.r, D.ffn, L->thr_logit,
-                                          scores, mask_words));
+                                          scores, mask_words, L->always_on / 64));
     }
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
@@ -563,7 +570,7 @@ pf_status launch_layer_fused(pf_ctx *ctx, const pf_layer *L, const float *x, con
                              (const float *)ctx->t, w_up, w_gate, L->w.b_up, x_in, D.r, D.d,      \
                              D.ffn, pf::h_stride(B), L->thr_logit, ctx->seg_strided != 0,         \
                              ctx->mask_words2,                                                    \
-                             reinterpret_cast<uint8_t *>(ctx->idx), ctx->h, up_floor_of(D)))
+                             reinterpret_cast<uint8_t *>(ctx->idx), ctx->h, up_floor_of(D), L->always_on))
         if (gated) { PF_OU(1); } else { PF_OU(0); }
 #undef PF_OU
     }
@@ -765,7 +772,7 @@ pf_status stack_enqueue_lookahead_merged(pf_ctx *ctx, pf_layer *const *layers, i
         if (P < 1) P = 1;
         if (ctx->down_split == 0 && P > 2) P = 2;
         if (P > pf::kDown2MaxSplit) P = pf::kDown2MaxSplit;
-        const int n_out = N ? N->desc.ffn / pf::kLaOutNeurons : 0;
+        const int n_out = N ? (N->desc.ffn - N->always_on) / pf::kLaOutNeurons : 0;
         const size_t lds2 = N ? ((size_t)B * kpad_of(N->desc.r) + pf::kStageScrap) * sizeof(float) : 0;
         {
             ProfScope ps(ctx, K_LA_DOWN_OUT);
@@ -777,7 +784,7 @@ pf_status stack_enqueue_lookahead_merged(pf_ctx *ctx, pf_layer *const *layers, i
                                       static_cast<const __half *>(N ? N->w.p2 : nullptr),
                                       N ? N->w.p_bias : nullptr, (const float *)ctx->t,
                                       N ? N->desc.r : 0, N ? N->desc.ffn : 0, N ? N->thr_logit : 0.f,
-                                      masks[(l + 1) & 1], false));
+                                      masks[(l + 1) & 1], N ? N->always_on / 64 : 0, false));
         }
         ny = P;
         PF_HIP(ctx, hipGetLastError());
@@ -897,14 +904,38 @@ __global__ void k_iota(int32_t *idx, int n, int32_t *count)
     if (i == 0) *count = n;
 }
 
-// counts[idx[j]] += 1 for j < *count: every neuron is listed at most once
+// counts[id(idx[j])] += 1 for j < *count, id = the layer's neuron table (stored -> original
+// number) or the identity: every neuron is listed at most once and the table is a permutation
 __global__ void k_count_activations(const int32_t *__restrict__ idx, const int32_t *__restrict__ count_p,
-                                    int ffn, uint32_t *__restrict__ counts)
+                                    int ffn, const int32_t *__restrict__ table,
+                                    uint32_t *__restrict__ counts)
 {
     const int n = min(max(*count_p, 0), ffn);
     for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < n; j += gridDim.x * blockDim.x) {
-        const int i = idx[j];
+        int i = idx[j];
+        if ((unsigned)i < (unsigned)ffn && table) i = table[i];
         if ((unsigned)i < (unsigned)ffn) counts[i] += 1u;
+    }
+}
+
+__global__ void k_zero_words(uint64_t *__restrict__ words, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) words[i] = 0ull;
+}
+
+// Mask words in the original neuron numbering from a list in stored numbering: bit
+// table[idx[j]] is set for j < *count.  Setting bits commutes, so the atomic OR leaves the
+// same words whatever the order.
+__global__ void k_scatter_original(const int32_t *__restrict__ idx, const int32_t *__restrict__ count_p,
+                                   int ffn, const int32_t *__restrict__ table,
+                                   uint32_t *__restrict__ words32)
+{
+    const int n = min(max(*count_p, 0), ffn);
+    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < n; j += gridDim.x * blockDim.x) {
+        int i = idx[j];
+        if ((unsigned)i < (unsigned)ffn && table) i = table[i];
+        if ((unsigned)i < (unsigned)ffn) atomicOr(&words32[i >> 5], 1u << (i & 31));
     }
 }
 
@@ -1179,7 +1210,36 @@ pf_status pf_count_activations(pf_ctx *ctx, const pf_layer *layer, uint32_t *cou
     if (layer->ctx != ctx) return fail(ctx, PF_EINVAL, "layer belongs to another context");
     if (!ctx->last_idx) return fail(ctx, PF_EINVAL, "no layer step has run on this context");
     hipLaunchKernelGGL(k_count_activations, dim3(64), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       ctx->last_idx, ctx->last_count, layer->desc.ffn, counts);
+                       ctx->last_idx, ctx->last_count, layer->desc.ffn, layer->table, counts);
+    PF_HIP(ctx, hipGetLastError());
+    return PF_OK;
+}
+
+pf_status pf_layer_set_neuron_table(pf_layer *layer, const int32_t *stored_to_original, int always_on)
+{
+    if (!layer) return PF_EINVAL;
+    pf_ctx *ctx = layer->ctx;
+    if (always_on < 0 || always_on % 64 != 0 || always_on > layer->desc.ffn - 64)
+        return fail(ctx, PF_EINVAL, "always_on %d: a multiple of 64 in [0, ffn - 64]", always_on);
+    layer->table = stored_to_original;
+    layer->always_on = always_on;
+    return PF_OK;
+}
+
+pf_status pf_layer_active_original(pf_ctx *ctx, const pf_layer *layer, uint64_t *mask_words,
+                                   int32_t *idx, int32_t *count, void *stream)
+{
+    if (!ctx) return PF_EINVAL;
+    if (!layer || !mask_words || !idx || !count) return fail(ctx, PF_EINVAL, "null argument");
+    if (layer->ctx != ctx) return fail(ctx, PF_EINVAL, "layer belongs to another context");
+    if (!ctx->last_idx) return fail(ctx, PF_EINVAL, "no layer step has run on this context");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int nwords = layer->desc.ffn / 64;
+    hipLaunchKernelGGL(k_zero_words, dim3(cdiv(nwords, 256)), dim3(256), 0, st, mask_words, nwords);
+    hipLaunchKernelGGL(k_scatter_original, dim3(64), dim3(256), 0, st, ctx->last_idx, ctx->last_count,
+                       layer->desc.ffn, layer->table, reinterpret_cast<uint32_t *>(mask_words));
+    hipLaunchKernelGGL(pf::k_compact, dim3(1), dim3(pf::kCompactThreads), 0, st,
+                       (const uint64_t *)mask_words, nwords, idx, count);
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
 }

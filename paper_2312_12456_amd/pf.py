@@ -24,6 +24,7 @@ EXPORTS = [
     "pf_last_error", "pf_version", "pf_profile_begin", "pf_profile_end", "pf_dense_ffn",
     "pf_layer_step_auto", "pf_count_activations", "pf_ctx_set_lookahead", "pf_ctx_set_option",
     "pf_ctx_get_option", "pf_ctx_set_mask_trace", "pf_layer_step_noalloc",
+    "pf_layer_set_neuron_table", "pf_layer_active_original",
 ]
 
 # pf_option keys
@@ -84,6 +85,8 @@ def lib():
         L.pf_ctx_set_option.argtypes = [P, I, I]
         L.pf_ctx_get_option.argtypes = [P, I, ctypes.POINTER(I)]
         L.pf_ctx_set_mask_trace.argtypes = [P, P, I]
+        L.pf_layer_set_neuron_table.argtypes = [P, P, I]
+        L.pf_layer_active_original.argtypes = [P, P, P, P, P, P]
         L.pf_layer_step_noalloc.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(LayerWeights),
                                             P, I, P, P]
         L.pf_stack_glue.argtypes = [P, P, P, I, I, P, P]
@@ -212,6 +215,12 @@ class Context:
                 self._h, _dev_ptr(trace, torch.int64, n_layers * (self.max_ffn // 64)), n_layers))
         self._trace = trace  # keeps the buffer alive while the library may write to it
 
+    def active_original(self, layer, mask_words, idx, count, stream=None):
+        """Last active set in the model's neuron numbering (through the layer's neuron table)."""
+        self.check(lib().pf_layer_active_original(
+            self._h, layer._h, _dev_ptr(mask_words, torch.int64, layer.ffn // 64),
+            _dev_ptr(idx, torch.int32, layer.ffn), _dev_ptr(count, torch.int32, 1), _stream_ptr(stream)))
+
     def last_active(self):
         """(mask_words, idx, count) device addresses left by the last layer_step."""
         m, i, c = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
@@ -270,6 +279,13 @@ class Layer:
                    w_up=g("w_up"), w_gate=g("w_gate"), w_down=g("w_down"), s_up=g("s_up"),
                    s_gate=g("s_gate"), s_down=g("s_down"), b_up=g("b_up"), b_down=g("b_down"),
                    p1=g("p1"), p2=g("p2"), p_bias=g("p_bias"))
+
+    def set_neuron_table(self, stored_to_original, always_on=0):
+        """stored_to_original: int32 device tensor [ffn] (a permutation) or None; always_on: length
+        of the stored prefix that is listed without being predicted (a multiple of 64)."""
+        self.ctx.check(lib().pf_layer_set_neuron_table(
+            self._h, _dev_ptr(stored_to_original, torch.int32, self.ffn), int(always_on)))
+        self._table = stored_to_original  # borrowed by the library: keep it alive
 
     def close(self):
         if self._h:

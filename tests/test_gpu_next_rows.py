@@ -6,7 +6,8 @@ import pytest
 import torch
 
 from paper_2312_12456_amd import workload as wl
-from tests.util import MaskTrace, check_output, oracle_layer, small_cfg
+from tests.util import (MaskTrace, check_active_set, check_output, oracle_chain_on_device_sets,
+                        oracle_layer, small_cfg, words_to_mask)
 
 pytestmark = pytest.mark.gpu
 
@@ -250,3 +251,137 @@ def test_repeated_runs_are_bit_identical(pf, B):
     ctx.layer_step(Ls[0], x, y2)
     torch.cuda.synchronize()
     assert torch.equal(y1, y2)
+
+
+def _hot_first(pf, ctx, cfg, lay, seed, tokens=32):
+    """Profile a layer with the library's activation counter and return (order, permuted
+    tensors): stored position j holds the model's neuron order[j], hottest first."""
+    L = pf.Layer.from_workload(ctx, cfg, lay)
+    counts = torch.zeros(cfg.ffn, dtype=torch.int32, device="cuda")
+    y = torch.empty((1, cfg.d), device="cuda")
+    for t in range(tokens):
+        ctx.layer_step(L, wl.make_inputs(cfg, 100 + t, seed=seed, batch=1, device="cuda"), y)
+        ctx.count_activations(L, counts)
+    torch.cuda.synchronize()
+    order = torch.argsort(counts, descending=True, stable=True).cpu().numpy()
+    return order, wl.permute_neurons(lay, order)
+
+
+@pytest.mark.parametrize("B", [1, 4])
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU])
+def test_neuron_table_and_always_on_prefix(pf, oracle, act, B):
+    """A layer stored hot-first with its neuron table (stored -> model numbering) and an
+    always-on prefix of 128 neurons, against the oracle on the layer as the model numbers it:
+    the set the library reports in model numbering is the oracle's prediction outside the score
+    band plus the prefix, the list is its compaction, the output is the oracle's FFN over that
+    set; the prefix is listed without its predictor rows being evaluated (scores read 1), and
+    the activation counter counts in model numbering."""
+    cfg = small_cfg(d=520, ffn=1344, r=136, act=act, rate=0.12)
+    A = 128
+    lay = wl.make_layer(cfg, 0, seed=77 + act, device="cuda")
+    O = oracle_layer(cfg, wl.to_host(lay))           # the layer in the model's numbering
+    ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
+    order, perm = _hot_first(pf, ctx, cfg, lay, seed=77)
+    assert sorted(order.tolist()) == list(range(cfg.ffn))
+    table = torch.from_numpy(order.astype(np.int32)).cuda()
+    LP = pf.Layer.from_workload(ctx, cfg, perm)
+    LP.set_neuron_table(table, A)
+    forced = np.zeros(cfg.ffn, bool)
+    forced[order[:A]] = True
+    words = torch.empty(cfg.ffn // 64, dtype=torch.int64, device="cuda")
+    idx = torch.empty(cfg.ffn, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+    counts = torch.zeros(cfg.ffn, dtype=torch.int32, device="cuda")
+    col_sums = np.zeros(cfg.ffn, np.int64)
+    for t in range(3):
+        x = wl.make_inputs(cfg, t, seed=78, batch=B, device="cuda")
+        xh = x.cpu().numpy()
+        y = torch.full((B, cfg.d), float("nan"), device="cuda")
+        ctx.layer_step(LP, x, y)
+        ctx.active_original(LP, words, idx, cnt)
+        ctx.count_activations(LP, counts)
+        torch.cuda.synchronize()
+        used = words_to_mask(words.cpu().numpy(), cfg.ffn)
+        check_active_set(used, O.predict(xh)["scores"], cfg.threshold, "table token %d" % t,
+                         always_on=forced)
+        assert np.array_equal(idx.cpu().numpy()[:int(cnt.item())], np.flatnonzero(used))
+        check_output(y.cpu().numpy(), O.masked_ffn(xh, used), "layer with neuron table")
+        col_sums += used
+        # in stored numbering the prefix is the first A bits, and their scores read 1
+        sc = torch.full((B, cfg.ffn), -1.0, device="cuda")
+        w2 = torch.zeros(cfg.ffn // 64, dtype=torch.int64, device="cuda")
+        ctx.predict(LP, x, sc, w2)
+        torch.cuda.synchronize()
+        stored = words_to_mask(w2.cpu().numpy(), cfg.ffn)
+        assert stored[:A].all() and bool((sc[:, :A] == 1).all())
+        assert np.array_equal(stored, used[order])
+        ref_sc = O.predict(xh)["scores"][:, order]
+        np.testing.assert_allclose(sc.cpu().numpy()[:, A:], ref_sc[:, A:], atol=2e-5, rtol=0)
+    assert np.array_equal(counts.cpu().numpy(), col_sums)
+    with pytest.raises(pf.PfError):
+        LP.set_neuron_table(table, 100)           # not a multiple of 64
+    with pytest.raises(pf.PfError):
+        LP.set_neuron_table(table, cfg.ffn)       # at least one word stays predicted
+    LP.set_neuron_table(None, 0)                  # back to a plain layer in stored numbering
+
+
+@pytest.mark.parametrize("form", ["list", "fused", "fused-strided", "lookahead"])
+def test_stack_of_hot_first_layers_with_always_on_prefix(pf, oracle, form):
+    """Three hot-first layers with neuron tables and always-on prefixes through pf_stack_step in
+    every form the stack has (list form, three-launch form with both segment layouts, two-launch
+    look-ahead): the mask trace (stored numbering) mapped through the tables against the
+    oracle's stack on the layers as the model numbers them."""
+    from tests.util import oracle_lookahead_chain_on_device_sets
+    cfg = small_cfg(d=520, ffn=1344, r=136, rate=0.12, layers=3)
+    B, A = 2, 192
+    ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
+    ctx.set_option(pf.OPT_FUSED, 0 if form == "list" else 2)
+    ctx.set_option(pf.OPT_SEG_STRIDED, 1 if form == "fused-strided" else 0)
+    ctx.set_lookahead(1 if form == "lookahead" else 0)
+    lays = [wl.make_layer(cfg, l, seed=81, device="cuda") for l in range(cfg.layers)]
+    Os = [oracle_layer(cfg, wl.to_host(t)) for t in lays]
+    Ls, orders, keep = [], [], []
+    for t in lays:
+        ctx.set_lookahead(0)
+        order, perm = _hot_first(pf, ctx, cfg, t, seed=81, tokens=16)
+        table = torch.from_numpy(order.astype(np.int32)).cuda()
+        L = pf.Layer.from_workload(ctx, cfg, perm)
+        L.set_neuron_table(table, A)
+        Ls.append(L)
+        orders.append(order)
+        keep.append((perm, table))
+    ctx.set_lookahead(1 if form == "lookahead" else 0)
+    x0 = wl.make_inputs(cfg, 0, seed=82, batch=B, device="cuda")
+    trace = MaskTrace(ctx, cfg.layers, cfg.ffn)
+    out = torch.full_like(x0, float("nan"))
+    ctx.profile_begin()
+    ctx.stack_step(Ls, x0, out)
+    stats = ctx.profile_end()
+    torch.cuda.synchronize()
+    ctx.set_mask_trace(None)
+    if form.startswith("fused"):
+        assert stats["k_out_up"][0] == cfg.layers - 1
+    if form == "lookahead":
+        assert stats["k_la_down_out"][0] == cfg.layers
+    masks, forced = [], []
+    for l, m in enumerate(trace.masks()):
+        assert m[:A].all()                         # the prefix, in stored numbering
+        orig = np.zeros(cfg.ffn, bool)
+        orig[orders[l]] = m
+        masks.append(orig)
+        f = np.zeros(cfg.ffn, bool)
+        f[orders[l][:A]] = True
+        forced.append(f)
+    if form == "lookahead":
+        xo, inputs = x0.cpu().numpy(), []
+        for l, (O, m) in enumerate(zip(Os, masks)):
+            inputs.append(xo)
+            seen = inputs[0] if l == 0 else inputs[l - 1]
+            check_active_set(m, O.predict(seen)["scores"], cfg.threshold, "layer %d" % l, forced[l])
+            xo = oracle.stack_glue(xo, O.masked_ffn(xo, m))
+        ref = xo
+    else:
+        ref, n_cmp, _ = oracle_chain_on_device_sets(oracle, Os, x0.cpu().numpy(), masks, cfg.threshold,
+                                                    form, always_on=forced)
+        assert n_cmp == cfg.layers
+    check_output(out.cpu().numpy(), ref, "hot-first stack, " + form)

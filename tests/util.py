@@ -40,8 +40,9 @@ def check_output(y_dev, y_ref, what=""):
     return err
 
 
-def check_active_set(dev_mask, ref_scores, threshold, what=""):
-    """Bit-exact union mask outside the 1e-3 score band around the threshold."""
+def check_active_set(dev_mask, ref_scores, threshold, what="", always_on=None):
+    """Bit-exact union mask outside the 1e-3 score band around the threshold.  Neurons of an
+    always-on set (listed without prediction) must be on and are otherwise not compared."""
     ref_scores = np.atleast_2d(ref_scores)
     ref_rows = ref_scores > threshold
     ref_mask = ref_rows.any(axis=0)
@@ -50,6 +51,10 @@ def check_active_set(dev_mask, ref_scores, threshold, what=""):
     in_band = np.abs(ref_scores - threshold) < SCORE_BAND
     decided_on = (ref_rows & ~in_band).any(axis=0)
     comparable = decided_on | ~in_band.any(axis=0)
+    if always_on is not None:
+        always_on = np.asarray(always_on, bool)
+        assert np.asarray(dev_mask, bool)[always_on].all(), "%s: an always-on neuron is off" % what
+        comparable &= ~always_on
     bad = comparable & (np.asarray(dev_mask, bool) != ref_mask)
     assert not bad.any(), "%s: %d active-set mismatches outside the band, first %s" % (
         what, int(bad.sum()), np.flatnonzero(bad)[:8])
@@ -76,7 +81,7 @@ class MaskTrace:
         return [words_to_mask(host[l, :self.ffn // 64], self.ffn) for l in range(self.n_layers)]
 
 
-def oracle_chain_on_device_sets(oracle_mod, Os, x0, masks, threshold, what=""):
+def oracle_chain_on_device_sets(oracle_mod, Os, x0, masks, threshold, what="", always_on=None):
     """The oracle's stack driven by the active sets the device used, layer by layer: the set of
     layer l must equal the oracle's prediction on the oracle's own input to that layer outside
     the score band; the oracle then runs its masked FFN on exactly that set, so a flip inside
@@ -86,7 +91,8 @@ def oracle_chain_on_device_sets(oracle_mod, Os, x0, masks, threshold, what=""):
     in_band = 0
     for l, (O, m) in enumerate(zip(Os, masks)):
         sc = O.predict(xo)["scores"]
-        in_band += check_active_set(m, sc, threshold, "%s layer %d" % (what, l))
+        in_band += check_active_set(m, sc, threshold, "%s layer %d" % (what, l),
+                                    None if always_on is None else always_on[l])
         xo = oracle_mod.stack_glue(xo, O.masked_ffn(xo, m))
     return xo, len(masks), in_band
 
