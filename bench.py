@@ -39,12 +39,15 @@ def parse_args():
     ap.add_argument("--config", default="opt-6.7b")
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--layers", type=int, default=None, help="override the layer count")
-    ap.add_argument("--mode", choices=["graph", "eager", "copycal", "m0", "floors"], default="graph",
+    ap.add_argument("--mode", choices=["graph", "eager", "copycal", "m0", "floors", "crossover"],
+                    default="graph",
                     help="copycal: only run plain device copies of a known size, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters by; m0: operator "
                          "micro-benchmark, one 4096 x 4096 layer, active fraction swept; "
                          "floors: latency-floor probes (empty kernel, dependent loads, plain "
-                         "streams from cache and from HBM, grid barrier) as graph nodes")
+                         "streams from cache and from HBM, grid barrier) as graph nodes; "
+                         "crossover: one layer of --config at --batch, sparse path against the "
+                         "dense path over the listed fraction (Sec. 8.2 dense fallback)")
     ap.add_argument("--sort-neurons", type=int, default=0, metavar="N",
                     help="profile activation counts over N tokens first and lay every layer's "
                          "neurons out hot-first (frequency-sorted layout)")
@@ -101,6 +104,92 @@ def operator_microbench(args, torch, np, pf, wl):
                      "fc2_GBps": round(by / dn_us / 1e3, 1)})
     return {"mode": "m0", "workload": "one layer, d=4096, ffn=4096, fp16, batch 1, uniformly "
             "random active rows, 64 launches per point", "points": rows}
+
+
+def crossover_table(args, torch, np, pf, wl):
+    """Where the dense fallback of Sec. 8.2 starts to pay: one layer of the configuration, the
+    predictor's time, the sparse kernels' time over uniformly random lists of swept size, the
+    dense step (every neuron listed, predictor skipped) and the dense step of the adaptive
+    entry point (predictor kernels launched but returning at once).  The crossover is the
+    listed fraction at which predictor + sparse kernels cost what the dense step costs."""
+    cfg = wl.scaled(wl.CONFIGS[args.config], layers=1)
+    B = args.batch
+    ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
+    lay = wl.make_layer(cfg, 0, args.seed, device="cuda")
+    L = pf.Layer.from_workload(ctx, cfg, lay)
+    x = wl.make_inputs(cfg, 0, args.seed, batch=B, device="cuda")
+    y = torch.empty_like(x)
+    words = torch.zeros(cfg.ffn // 64, dtype=torch.int64, device="cuda")
+    rng = np.random.Generator(np.random.PCG64(args.seed))
+    reps = 48
+
+    def timed(fn):
+        for _ in range(6):
+            fn()
+        torch.cuda.synchronize()
+        ctx.profile_begin()
+        for _ in range(reps):
+            fn()
+        st = ctx.profile_end()
+        return {k: round(1e3 * ms / n, 3) for k, (n, ms) in st.items() if n}, \
+            round(sum(1e3 * ms / reps for _, (n, ms) in st.items() if n), 3)
+
+    pred_k, pred_us = timed(lambda: ctx.predict(L, x, None, words))
+    dense_k, dense_us = timed(lambda: ctx.dense_ffn(L, x, y))
+    # adaptive entry point held in its dense mode (crossover so low that every step qualifies)
+    ctx.layer_step_adaptive(L, x, y, 1e-6)
+    ad_k, ad_us = timed(lambda: ctx.layer_step_adaptive(L, x, y, 1e-6))
+    L.adaptive_state(reset=True)
+    rows = []
+    for frac in (0.02, 0.05, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9, 1.0):
+        k = max(1, int(round(frac * cfg.ffn)))
+        sel = np.sort(rng.choice(cfg.ffn, size=k, replace=False)).astype(np.int32)
+        idx = torch.zeros(cfg.ffn, dtype=torch.int32, device="cuda")
+        idx[:k] = torch.from_numpy(sel).cuda()
+        cnt = torch.tensor([k], dtype=torch.int32, device="cuda")
+        sk, sus = timed(lambda: ctx.sparse_ffn(L, x, idx, cnt, y))
+        rows.append({"fraction": frac, "k": k, "sparse_us": sus, "predictor_plus_sparse_us": round(pred_us + sus, 3)})
+    cross = None
+    for a, b in zip(rows, rows[1:]):
+        fa, fb = a["predictor_plus_sparse_us"] - dense_us, b["predictor_plus_sparse_us"] - dense_us
+        if fa < 0 <= fb:
+            cross = round(a["fraction"] + (b["fraction"] - a["fraction"]) * (-fa) / (fb - fa), 3)
+            break
+    out = {"mode": "crossover", "workload": "one %s layer (d=%d, ffn=%d, r=%d), batch %d, uniformly "
+           "random lists, %d launches per point, per-kernel HIP events" % (cfg.name, cfg.d, cfg.ffn, cfg.r, B, reps),
+           "predictor_us": pred_us, "predictor_kernels": pred_k, "dense_us": dense_us,
+           "dense_kernels": dense_k, "adaptive_dense_step_us": ad_us, "adaptive_dense_kernels": ad_k,
+           "points": rows, "crossover_fraction": cross}
+    if B == 1 and cfg.wtype == wl.W_FP16 and cfg.ffn >= 8192:
+        # a plain streaming GEMV over the first 8192 rows of FC1 (the predictor's hidden-layer
+        # kernel: rows in order, no list) against the gather kernel over the list 0 .. 8191
+        ctx2 = pf.Context(cfg.d, 8192, 8192, max_batch=1)
+        w8 = lay["w_up"][:8192].contiguous()
+        Ls = pf.Layer(ctx2, cfg.d, 8192, 8192, w_up=w8, w_down=w8, p1=w8,
+                      p2=torch.zeros((8192, 8192), dtype=torch.float16, device="cuda"))
+        w2 = torch.zeros(128, dtype=torch.int64, device="cuda")
+        sk, _ = timed_on(ctx2, lambda: ctx2.predict(Ls, x, None, w2), torch, reps)
+        idx = torch.arange(8192, dtype=torch.int32, device="cuda")
+        cnt = torch.tensor([8192], dtype=torch.int32, device="cuda")
+        y2 = torch.empty_like(x)
+        gk, _ = timed_on(ctx2, lambda: ctx2.sparse_ffn(Ls, x, idx, cnt, y2), torch, reps)
+        by = 8192 * cfg.row_bytes
+        out["stream_vs_gather_8192_rows"] = {
+            "bytes": by, "stream_gemv_us": sk["k_pred_hidden"], "gather_over_iota_us": gk["k_up"],
+            "stream_GBps": round(by / sk["k_pred_hidden"] / 1e3, 1),
+            "gather_GBps": round(by / gk["k_up"] / 1e3, 1)}
+    return out
+
+
+def timed_on(ctx, fn, torch, reps):
+    for _ in range(6):
+        fn()
+    torch.cuda.synchronize()
+    ctx.profile_begin()
+    for _ in range(reps):
+        fn()
+    st = ctx.profile_end()
+    return {k: round(1e3 * ms / n, 3) for k, (n, ms) in st.items() if n}, None
 
 
 def _probe_lib():
@@ -206,6 +295,9 @@ def main():
         return
     if args.mode == "m0":
         print(json.dumps(operator_microbench(args, torch, np, pf, wl)))
+        return
+    if args.mode == "crossover":
+        print(json.dumps(crossover_table(args, torch, np, pf, wl)))
         return
     cfg = wl.CONFIGS[args.config]
     if args.layers:

@@ -100,7 +100,8 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
 void pf_ctx_destroy(pf_ctx *ctx);
 
 /* Layer: validates the descriptor against the context and records the borrowed weight
- * pointers (nothing is copied or launched).  p1/p2 may be NULL for a layer that is only
+ * pointers (no weight is copied and nothing is launched; the layer owns 256 bytes of device
+ * state for pf_layer_step_adaptive).  p1/p2 may be NULL for a layer that is only
  * used with pf_sparse_ffn. */
 pf_status pf_layer_create(pf_ctx *ctx, const pf_layer_desc *desc, const pf_layer_weights *w,
                           pf_layer **out);
@@ -171,6 +172,25 @@ pf_status pf_dense_ffn(pf_ctx *ctx, const pf_layer *layer, const float *x, int B
  * outside (0, 1] or a negative hint. */
 pf_status pf_layer_step_auto(pf_ctx *ctx, const pf_layer *layer, const float *x, int B,
                              float density_hint, float crossover, float *y, void *stream);
+
+/* Layer step that takes the dense decision of Sec. 8.2 on the DEVICE: the layer keeps a few
+ * words of device state -- how many neurons the previous adaptive step of this layer saw, and
+ * whether that was at least crossover * ffn.  If so this step runs dense: the predictor's
+ * kernels return at once (their cost is not paid) and every neuron is listed; otherwise it is
+ * pf_layer_step.  A sparse step sees the size of its predicted list; a dense step computes
+ * every neuron and therefore sees the exact number of neurons whose FC1 output is non-zero
+ * for some token -- which is what lets the layer fall back to the sparse path when the
+ * density drops again.  Nothing is copied to the host and the same launches are enqueued in
+ * both modes, so the call can be recorded into a HIP graph.  The first step of a layer is
+ * sparse.  crossover: fraction in (0, 1].  Errors as pf_layer_step. */
+pf_status pf_layer_step_adaptive(pf_ctx *ctx, pf_layer *layer, const float *x, int B, float crossover,
+                                 float *y, void *stream);
+
+/* The adaptive state of a layer, for inspection: host_state[0] = 1 if the next adaptive step
+ * will run dense, [1] = neurons seen at the last one, [2] = 1 if the last one ran dense.
+ * Synchronises with the device (a test and tuning aid, not for the token loop).  reset != 0
+ * puts the layer back into its initial state afterwards.  host_state may be NULL. */
+pf_status pf_layer_adaptive_state(pf_layer *layer, int32_t *host_state, int reset);
 
 /* Activation profiler (the counting of Sec. 6.1 that fills the neuron table): counts[i] += 1
  * for every neuron i -- in the model's numbering when the layer has a neuron table -- of the

@@ -345,10 +345,19 @@ template <int R, int KC, int EPI>
 __global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
     const __half *__restrict__ w, const float *__restrict__ v, int B, int K, int nrows,
     const float *__restrict__ p_bias, float thr_logit, float *__restrict__ out,
-    uint64_t *__restrict__ mask_words, int first_word)
+    uint64_t *__restrict__ mask_words, int first_word, const int32_t *__restrict__ skip)
 {
     extern __shared__ uint64_t dyn_lds64[];
     constexpr int T = (R + 15) / 16;  // MFMA tiles per block
+    // adaptive layer step: a set flag means this step runs dense (no prediction; all marked)
+    if (skip != nullptr && *skip != 0) {
+        if (EPI == 1) {
+            if (threadIdx.x == 0) mask_words[first_word + (int)blockIdx.x] = ~0ull;
+            if (blockIdx.x == 0)
+                for (int w = threadIdx.x; w < first_word; w += kMfmaThreads) mask_words[w] = ~0ull;
+        }
+        return;
+    }
     __shared__ float logit_s[16][16 * T];
     static_assert(R * KC * 2 == kRowsMfmaSlotBytes, "slot size");
     static_assert(EPI == 0 || R == 64, "the output layer writes one mask word per block");

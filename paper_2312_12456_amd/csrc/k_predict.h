@@ -180,10 +180,12 @@ __global__ __launch_bounds__(kPredThreads) void k_pred_hidden(const __half *__re
                                                               int ypstride,
                                                               float *__restrict__ x_new,
                                                               float *__restrict__ t, int d, int r,
-                                                              int b0)
+                                                              int b0, const int32_t *__restrict__ skip)
 {
     extern __shared__ float xs[];
     __shared__ float ss_w[kPredWaves][B];
+    // adaptive layer step: a set flag means this step runs dense and needs no prediction
+    if (skip != nullptr && *skip != 0) return;
     pred_hidden_body<B, GLUE, GS>(xs, ss_w, (int)blockIdx.x, blockIdx.x == 0, p1, x, yp, ny, ypstride,
                                   x_new, t, d, r, b0);
 }
@@ -291,10 +293,16 @@ template <int B>
 __global__ __launch_bounds__(kPredOutThreads) void k_pred_out(
     const __half *__restrict__ p2, const float *__restrict__ p_bias, const float *__restrict__ t,
     int r, int ffn, float thr_logit, float *__restrict__ scores, uint64_t *__restrict__ mask_words,
-    int first_word)
+    int first_word, const int32_t *__restrict__ skip)
 {
     extern __shared__ float ts[];  // [B][kpad] staged hidden vector
     __shared__ float logit_s[B][kPredOutNeurons];
+    // adaptive layer step: a set flag means this step runs dense -- every neuron is marked
+    if (skip != nullptr && *skip != 0) {
+        if (threadIdx.x == 0) mask_words[first_word + (int)blockIdx.x] = ~0ull;
+        if (blockIdx.x == 0 && first_word > 0) mark_always_on<B>(first_word, ffn, nullptr, mask_words);
+        return;
+    }
     pred_out_body<B, kPredOutNeurons>(ts, logit_s, (int)blockIdx.x, p2, p_bias, t, r, ffn, thr_logit,
                                       scores, mask_words, first_word);
 }

@@ -95,6 +95,8 @@ struct pf_layer {
     float thr_logit;
     const int32_t *table = nullptr;  // stored neuron -> original neuron (borrowed), or null
     int always_on = 0;               // stored neurons [0, always_on) are listed without prediction
+    int32_t *adapt = nullptr;        // device: {dense flag for the next adaptive step, neurons
+                                     // counted at the last one, mode of the last one}; owned
 };
 
 struct pf_plan {
@@ -286,7 +288,7 @@ inline bool pred_mfma(const pf_ctx *ctx, const pf_layer_desc &D, int K, int B)
 // Predictor hidden layer.  With glue_y the layer input is formed inside the kernel as
 // norm(x + glue_y) and also written to x_new.
 pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
-                        int glue_ny, float *x_new, int B, hipStream_t st)
+                        int glue_ny, float *x_new, int B, hipStream_t st, const int32_t *skip = nullptr)
 {
     const pf_layer_desc &D = L->desc;
     if (!L->w.p1 || !L->w.p2) return fail(ctx, PF_EINVAL, "layer has no predictor weights");
@@ -301,7 +303,7 @@ pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const fl
         ProfScope ps(ctx, K_PRED_HIDDEN);
         PF_LAUNCH(ps, (pf::k_rows_mfma<8, 512, 0>), dim3(cdiv(D.r, 8)), dim3(pf::kMfmaThreads),
                   (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p1, x, B, D.d, D.r,
-                  (const float *)nullptr, 0.f, ctx->t, (uint64_t *)nullptr, 0);
+                  (const float *)nullptr, 0.f, ctx->t, (uint64_t *)nullptr, 0, skip);
         PF_HIP(ctx, hipGetLastError());
         return PF_OK;
     }
@@ -316,17 +318,17 @@ pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const fl
         if (glue_y && bt == 1 && kpad_of(D.d) <= 4096) {  // the whole glue in one round trip
             PF_LAUNCH(ps, (pf::k_pred_hidden<1, true, 4>), grid, dim3(pf::kPredThreads), lds, st, p1,
                       x + xo, glue_y + xo, glue_ny, B * D.d, x_new + xo, ctx->t + (size_t)b0 * D.r, D.d,
-                      D.r, b0);
+                      D.r, b0, skip);
         } else if (glue_y) {
             PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_pred_hidden<BT, true>), grid,
                                                dim3(pf::kPredThreads), lds, st, p1, x + xo,
                                                glue_y + xo, glue_ny, B * D.d, x_new + xo,
-                                               ctx->t + (size_t)b0 * D.r, D.d, D.r, b0));
+                                               ctx->t + (size_t)b0 * D.r, D.d, D.r, b0, skip));
         } else {
             PF_SWITCH_B(bt, PF_LAUNCH(ps, (pf::k_pred_hidden<BT, false>), grid,
                                                dim3(pf::kPredThreads), lds, st, p1, x + xo,
                                                (const float *)nullptr, 0, 0, (float *)nullptr,
-                                               ctx->t + (size_t)b0 * D.r, D.d, D.r, b0));
+                                               ctx->t + (size_t)b0 * D.r, D.d, D.r, b0, skip));
         }
     }
     PF_HIP(ctx, hipGetLastError());
@@ -341,9 +343,9 @@ inline int pred_out_words(const pf_layer *L) { return L->desc.ffn / 64 - L->alwa
 // Predictor: hidden layer, then output layer + ballot into mask words.
 pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const float *glue_y,
                          int glue_ny, float *x_new, int B, float *scores, uint64_t *mask_words,
-                         hipStream_t st)
+                         hipStream_t st, const int32_t *skip = nullptr)
 {
-    pf_status s = launch_hidden(ctx, L, x, glue_y, glue_ny, x_new, B, st);
+    pf_status s = launch_hidden(ctx, L, x, glue_y, glue_ny, x_new, B, st, skip);
     if (s != PF_OK) return s;
     const pf_layer_desc &D = L->desc;
     const __half *p2 = static_cast<const __half *>(L->w.p2);
@@ -351,7 +353,7 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
         ProfScope ps(ctx, K_PRED_OUT);
         PF_LAUNCH(ps, (pf::k_rows_mfma<64, 64, 1>), dim3(pred_out_words(L)), dim3(pf::kMfmaThreads),
                   (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p2, (const float *)ctx->t, B, D.r,
-                  D.ffn, L->w.p_bias, L->thr_logit, scores, mask_words, L->always_on / 64);
+                  D.ffn, L->w.p_bias, L->thr_logit, scores, mask_words, L->always_on / 64, skip);
         PF_HIP(ctx, hipGetLastError());
         return PF_OK;
     }
@@ -362,7 +364,7 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
         ProfScope ps(ctx, K_PRED_OUT);
         PF_SWITCH_B(B, PF_LAUNCH(ps, pf::k_pred_out<BT>, grid, dim3(pf::kPredOutThreads), lds,
                                           st, p2, L->w.p_bias, ctx->t, D.r, D.ffn, L->thr_logit,
-                                          scores, mask_words, L->always_on / 64));
+                                          scores, mask_words, L->always_on / 64, skip));
     }
     PF_HIP(ctx, hipGetLastError());
     return PF_OK;
@@ -918,6 +920,38 @@ __global__ void k_count_activations(const int32_t *__restrict__ idx, const int32
     }
 }
 
+// After an adaptive layer step: the density seen at this step decides the mode of the next.
+// A sparse step saw the predicted list (its count); a dense step computed every neuron, so it
+// counts the neurons whose FC1 output is non-zero for some token -- the exact active set.
+// state = {dense flag, count, mode of this step}.  One workgroup.
+__global__ __launch_bounds__(1024) void k_adapt_update(int32_t *__restrict__ state,
+                                                       const int32_t *__restrict__ count_p,
+                                                       const float *__restrict__ h, int hs, int B,
+                                                       int ffn, int threshold_count)
+{
+    __shared__ int part[16];
+    const int dense = state[0];
+    int n = min(max(*count_p, 0), ffn);
+    if (dense) {  // uniform
+        int mine = 0;
+        for (int j = threadIdx.x; j < ffn; j += 1024) {
+            bool nz = false;
+            for (int b = 0; b < B; ++b) nz = nz || h[(size_t)j * hs + b] != 0.f;
+            mine += nz ? 1 : 0;
+        }
+        for (int o = 32; o >= 1; o >>= 1) mine += __shfl_xor(mine, o, 64);
+        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mine;
+        __syncthreads();
+        n = 0;
+        for (int k = 0; k < 16; ++k) n += part[k];
+    }
+    if (threadIdx.x == 0) {
+        state[1] = n;
+        state[2] = dense;
+        state[0] = n >= threshold_count ? 1 : 0;
+    }
+}
+
 __global__ void k_zero_words(uint64_t *__restrict__ words, int n)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1101,11 +1135,26 @@ pf_status pf_layer_create(pf_ctx *ctx, const pf_layer_desc *desc, const pf_layer
     L->desc = *desc;
     L->w = *w;
     L->thr_logit = logit_of(desc->threshold);
+    // the few words of device state of pf_layer_step_adaptive
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&L->adapt), 256);
+    if (e == hipSuccess) e = hipMemset(L->adapt, 0, 256);
+    if (e != hipSuccess) {
+        (void)hipFree(L->adapt);
+        delete L;
+        return fail(ctx, e == hipErrorOutOfMemory ? PF_ENOMEM : PF_EHIP, "layer state: %s",
+                    hipGetErrorString(e));
+    }
     *out = L;
     return PF_OK;
 }
 
-void pf_layer_destroy(pf_layer *layer) { delete layer; }
+void pf_layer_destroy(pf_layer *layer)
+{
+    if (!layer) return;
+    (void)hipFree(layer->adapt);
+    delete layer;
+}
 
 pf_status pf_predict(pf_ctx *ctx, const pf_layer *layer, const float *x, int B, float *scores,
                      uint64_t *mask_words, void *stream)
@@ -1201,6 +1250,44 @@ pf_status pf_layer_step_auto(pf_ctx *ctx, const pf_layer *layer, const float *x,
                     (double)crossover, (double)density_hint);
     if (density_hint >= crossover) return pf_dense_ffn(ctx, layer, x, B, y, stream);
     return pf_layer_step(ctx, layer, x, B, y, stream);
+}
+
+pf_status pf_layer_step_adaptive(pf_ctx *ctx, pf_layer *layer, const float *x, int B, float crossover,
+                                 float *y, void *stream)
+{
+    pf_status s = check_batch(ctx, layer, x, B);
+    if (s != PF_OK) return s;
+    if (!y) return fail(ctx, PF_EINVAL, "y is null");
+    if (!layer->w.p1) return fail(ctx, PF_EINVAL, "layer has no predictor weights");
+    if (!(crossover > 0.f && crossover <= 1.f))
+        return fail(ctx, PF_EINVAL, "crossover %g outside (0, 1]", (double)crossover);
+    if (!layer->adapt) return fail(ctx, PF_EINVAL, "layer has no adaptive state");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const pf_layer_desc &D = layer->desc;
+    // predictor kernels return at once, and mark every neuron, when the layer's flag is set
+    s = launch_predict(ctx, layer, x, nullptr, 0, nullptr, B, nullptr, ctx->mask_words, st, layer->adapt);
+    if (s != PF_OK) return s;
+    ctx->last_mask = ctx->mask_words;
+    ctx->last_idx = ctx->idx;
+    ctx->last_count = ctx->count;
+    s = launch_sparse(ctx, layer, x, B, nullptr, nullptr, ctx->mask_words, y, nullptr, st);
+    if (s != PF_OK) return s;
+    int thr = (int)std::ceil((double)crossover * (double)D.ffn);
+    if (thr < 1) thr = 1;
+    hipLaunchKernelGGL(k_adapt_update, dim3(1), dim3(1024), 0, st, layer->adapt,
+                       (const int32_t *)ctx->count, (const float *)ctx->h, pf::h_stride(B), B, D.ffn, thr);
+    PF_HIP(ctx, hipGetLastError());
+    return PF_OK;
+}
+
+pf_status pf_layer_adaptive_state(pf_layer *layer, int32_t *host_state, int reset)
+{
+    if (!layer || !layer->adapt) return PF_EINVAL;
+    pf_ctx *ctx = layer->ctx;
+    PF_HIP(ctx, hipDeviceSynchronize());
+    if (host_state) PF_HIP(ctx, hipMemcpy(host_state, layer->adapt, 3 * sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (reset) PF_HIP(ctx, hipMemset(layer->adapt, 0, 256));
+    return PF_OK;
 }
 
 pf_status pf_count_activations(pf_ctx *ctx, const pf_layer *layer, uint32_t *counts, void *stream)

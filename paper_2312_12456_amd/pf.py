@@ -24,7 +24,8 @@ EXPORTS = [
     "pf_last_error", "pf_version", "pf_profile_begin", "pf_profile_end", "pf_dense_ffn",
     "pf_layer_step_auto", "pf_count_activations", "pf_ctx_set_lookahead", "pf_ctx_set_option",
     "pf_ctx_get_option", "pf_ctx_set_mask_trace", "pf_layer_step_noalloc",
-    "pf_layer_set_neuron_table", "pf_layer_active_original",
+    "pf_layer_set_neuron_table", "pf_layer_active_original", "pf_layer_step_adaptive",
+    "pf_layer_adaptive_state",
 ]
 
 # pf_option keys
@@ -85,6 +86,8 @@ def lib():
         L.pf_ctx_set_option.argtypes = [P, I, I]
         L.pf_ctx_get_option.argtypes = [P, I, ctypes.POINTER(I)]
         L.pf_ctx_set_mask_trace.argtypes = [P, P, I]
+        L.pf_layer_step_adaptive.argtypes = [P, P, P, I, ctypes.c_float, P, P]
+        L.pf_layer_adaptive_state.argtypes = [P, ctypes.POINTER(ctypes.c_int32), I]
         L.pf_layer_set_neuron_table.argtypes = [P, P, I]
         L.pf_layer_active_original.argtypes = [P, P, P, P, P, P]
         L.pf_layer_step_noalloc.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(LayerWeights),
@@ -190,6 +193,12 @@ class Context:
                                             B, ctypes.c_float(density_hint), ctypes.c_float(crossover),
                                             _dev_ptr(y, torch.float32, B * layer.d), _stream_ptr(stream)))
 
+    def layer_step_adaptive(self, layer, x, y, crossover, stream=None):
+        B = x.shape[0]
+        self.check(lib().pf_layer_step_adaptive(self._h, layer._h, _dev_ptr(x, torch.float32, B * layer.d),
+                                                B, ctypes.c_float(crossover),
+                                                _dev_ptr(y, torch.float32, B * layer.d), _stream_ptr(stream)))
+
     def count_activations(self, layer, counts, stream=None):
         """counts [ffn] int32 on the device (non-negative values, read as uint32 by the library)."""
         self.check(lib().pf_count_activations(self._h, layer._h, _dev_ptr(counts, torch.int32, layer.ffn),
@@ -279,6 +288,12 @@ class Layer:
                    w_up=g("w_up"), w_gate=g("w_gate"), w_down=g("w_down"), s_up=g("s_up"),
                    s_gate=g("s_gate"), s_down=g("s_down"), b_up=g("b_up"), b_down=g("b_down"),
                    p1=g("p1"), p2=g("p2"), p_bias=g("p_bias"))
+
+    def adaptive_state(self, reset=False):
+        """(dense next step?, neurons seen at the last adaptive step, last step dense?); syncs."""
+        st = (ctypes.c_int32 * 3)()
+        self.ctx.check(lib().pf_layer_adaptive_state(self._h, st, 1 if reset else 0))
+        return bool(st[0]), int(st[1]), bool(st[2])
 
     def set_neuron_table(self, stored_to_original, always_on=0):
         """stored_to_original: int32 device tensor [ffn] (a permutation) or None; always_on: length

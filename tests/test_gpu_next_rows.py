@@ -385,3 +385,70 @@ def test_stack_of_hot_first_layers_with_always_on_prefix(pf, oracle, form):
                                                     form, always_on=forced)
         assert n_cmp == cfg.layers
     check_output(out.cpu().numpy(), ref, "hot-first stack, " + form)
+
+
+@pytest.mark.parametrize("B", [1, 4])
+@pytest.mark.parametrize("act,wtype", [(wl.ACT_RELU, wl.W_FP16), (wl.ACT_REGLU, wl.W_FP16),
+                                       (wl.ACT_RELU, wl.W_INT4_G128)])
+def test_adaptive_layer_step_switches_on_device_density(pf, oracle, act, wtype, B):
+    """pf_layer_step_adaptive (Sec. 8.2 dense fallback, decided on the device): a token sequence
+    whose densities straddle the crossover.  After every step the layer's device state is read
+    and checked against the oracle: a sparse step saw its predicted list (set bit-exact outside
+    the score band, output = oracle FFN over that set), a dense step listed every neuron
+    (output = oracle dense FFN) and counted the neurons that really fired; the flag for the
+    next step is count >= crossover * ffn, and the next step runs in that mode."""
+    d = 640 if wtype == wl.W_INT4_G128 else 520
+    cfg = small_cfg(d=d, ffn=1344, r=136, act=act, wtype=wtype, rate=0.3)
+    ctx, L, O, _ = _setup(pf, cfg, seed=91 + act + B, max_batch=B)
+    T = 12
+    # inputs of varying norm: longer vectors open more neurons (predicted and real alike), so
+    # the density moves across any crossover placed between the extremes
+    norm = [1.0, 1.7, 1.7, 0.5, 0.5, 1.7, 1.7, 0.5, 0.5, 1.7, 0.5, 1.0]
+    xs = [wl.make_inputs(cfg, t, seed=92, batch=B, device="cuda") * norm[t] for t in range(T)]
+    pred = [int(O.predict(x.cpu().numpy())["active"].sum()) for x in xs]
+    fired = [int(O.exact_mask(x.cpu().numpy()).sum()) for x in xs]
+    # a threshold count for which the oracle's own run of the state machine goes both ways
+    thr = None
+    for cand in range(min(pred + fired), max(pred + fired) + 2):
+        dense, ups, downs = False, 0, 0
+        for t in range(T):
+            nxt = (fired[t] if dense else pred[t]) >= cand
+            ups += (not dense) and nxt
+            downs += dense and (not nxt)
+            dense = nxt
+        if ups >= 2 and downs >= 2:
+            thr = cand
+            break
+    assert thr is not None, (pred, fired)
+    crossover = (thr - 0.5) / cfg.ffn
+    assert L.adaptive_state() == (False, 0, False)
+    dense, seen = False, {True: 0, False: 0}
+    y = torch.empty((B, cfg.d), device="cuda")
+    for t in range(T):
+        xh = xs[t].cpu().numpy()
+        y.fill_(float("nan"))
+        ctx.layer_step_adaptive(L, xs[t], y, crossover)
+        nxt, cnt, was_dense = L.adaptive_state()
+        assert was_dense == dense, "step %d ran in the wrong mode" % t
+        seen[dense] += 1
+        wptr, lst = _last_list(pf, ctx, cfg.ffn)
+        if dense:
+            assert np.array_equal(lst, np.arange(cfg.ffn))
+            check_output(y.cpu().numpy(), O.dense_ffn(xh), "adaptive, dense step %d" % t)
+            pre = O.preact(xh)
+            unsure = int((np.abs(pre) < 1e-4).any(axis=0).sum())   # fp32 sign of a near-zero sum
+            assert abs(cnt - fired[t]) <= unsure, (cnt, fired[t], unsure)
+        else:
+            mask = np.zeros(cfg.ffn, bool)
+            mask[lst] = True
+            check_active_set(mask, O.predict(xh)["scores"], cfg.threshold, "adaptive step %d" % t)
+            assert cnt == lst.size
+            check_output(y.cpu().numpy(), O.masked_ffn(xh, mask), "adaptive, sparse step %d" % t)
+        assert nxt == (cnt >= thr)
+        dense = nxt
+    assert seen[True] >= 2 and seen[False] >= 2, seen
+    # reset: the next step is sparse again
+    assert L.adaptive_state(reset=True)[1] > 0
+    assert L.adaptive_state() == (False, 0, False)
+    with pytest.raises(pf.PfError):
+        ctx.layer_step_adaptive(L, xs[0], y, 0.0)
