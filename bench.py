@@ -358,6 +358,8 @@ def main():
         torch.cuda.synchronize()
         sort_info = {"profiled_tokens": n_prof, "always_on_mean": float(np.mean(prefix))}
 
+    if os.environ.get("PF_X_LA_FORM"):
+        ctx.set_option(pf.OPT_LOOKAHEAD_FORM, int(os.environ["PF_X_LA_FORM"]))
     ctx.set_lookahead(args.lookahead)
     plan = pf.Plan(ctx, layers, x_buf, out) if args.mode == "graph" else None
 

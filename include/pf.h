@@ -233,7 +233,8 @@ pf_status pf_ctx_last_active(pf_ctx *ctx, const uint64_t **mask_words, const int
  * FFN) instead of their sum.  With fp16 weights up to batch 3 a layer then runs as two
  * launches whose block ranges play two roles (hidden layer of the next predictor beside FC1;
  * FC2 beside the next predictor's output layer); otherwise the predictors run on a second
- * stream of the library beside the sparse kernels of the layer before.  This changes which neurons are listed
+ * stream of the library or follow the sparse kernels of the layer before on the same stream,
+ * whichever measured faster for the shape.  This changes which neurons are listed
  * (an approximation whose accuracy depends on trained predictors and is not measured here);
  * every other call is unaffected.  distance: 0 (off, the default) or 1. */
 pf_status pf_ctx_set_lookahead(pf_ctx *ctx, int distance);
@@ -253,8 +254,9 @@ pf_status pf_ctx_set_lookahead(pf_ctx *ctx, int distance);
  *   PF_OPT_UP_GRID          workgroups of the vector FC1 kernel (default 8 per CU; int4: 2)
  *   PF_OPT_MFMA_GRID        workgroups of the matrix-core FC1 kernel (default one per CU)
  *   PF_OPT_DOWN_SPLIT       row groups of FC2, 1 .. 4 (default CUs / column tiles, at most 4)
- *   PF_OPT_LOOKAHEAD_MERGED look-ahead stacks in two launches per layer where that form applies
- *                           (see pf_ctx_set_lookahead): 1 (default) / 0 = always two streams
+ *   PF_OPT_LOOKAHEAD_FORM   how a look-ahead stack is scheduled (see pf_ctx_set_lookahead):
+ *                           0 automatic (default), 1 two launches per layer where that form
+ *                           applies, 2 predictors on a second stream, 3 everything on one stream
  * Errors: PF_EINVAL for an unknown key or a value outside the stated range. */
 typedef enum {
     PF_OPT_FUSED = 0,
@@ -264,7 +266,7 @@ typedef enum {
     PF_OPT_UP_GRID = 4,
     PF_OPT_MFMA_GRID = 5,
     PF_OPT_DOWN_SPLIT = 6,
-    PF_OPT_LOOKAHEAD_MERGED = 7
+    PF_OPT_LOOKAHEAD_FORM = 7
 } pf_option;
 pf_status pf_ctx_set_option(pf_ctx *ctx, int key, int value);
 pf_status pf_ctx_get_option(const pf_ctx *ctx, int key, int *value);

@@ -58,7 +58,8 @@ struct pf_ctx {
     int fused = 1;                 // PF_OPT_FUSED: inner layers of a stack as three launches (0 never,
                                    // 1 where measured faster, 2 wherever possible)
     int seg_strided = 0;           // PF_OPT_SEG_STRIDED: strided segments (models stored hot-first)
-    int la_merged = 1;             // PF_OPT_LOOKAHEAD_MERGED: look-ahead in two launches per layer
+    int la_form = 0;               // PF_OPT_LOOKAHEAD_FORM: 0 automatic, 1 two launches per layer,
+                                   // 2 second stream, 3 one stream
 
     uint64_t *mask_trace = nullptr;  // caller's buffer for every layer's mask words (or null)
     int mask_trace_layers = 0;
@@ -704,6 +705,40 @@ pf_status stack_enqueue_lookahead(pf_ctx *ctx, pf_layer *const *layers, int n_la
     return launch_glue(ctx, cur, ctx->ypart, ny, d, B, x_out, st);
 }
 
+// Look-ahead prediction on one stream: the predictor of layer l+2 follows the sparse kernels of
+// layer l, and its hidden kernel forms the input of layer l+1 (the glue) on the way, so the
+// launches are those of the default schedule with the masks taken one layer earlier.
+pf_status stack_enqueue_lookahead_serial(pf_ctx *ctx, pf_layer *const *layers, int n_layers,
+                                         const float *x, int B, float *x_out, hipStream_t st)
+{
+    uint64_t *masks[2] = {ctx->mask_words, ctx->mask_words2};
+    const int d = layers[0]->desc.d;
+    pf_status s = launch_predict(ctx, layers[0], x, nullptr, 0, nullptr, B, nullptr, masks[0], st);
+    if (s == PF_OK && n_layers > 1)
+        s = launch_predict(ctx, layers[1], x, nullptr, 0, nullptr, B, nullptr, masks[1], st);
+    if (s != PF_OK) return s;
+    int ny = 1;
+    const float *cur = x;
+    for (int l = 0; l < n_layers; ++l) {
+        ctx->last_mask = masks[l & 1];
+        ctx->last_idx = ctx->idx;
+        ctx->last_count = ctx->count;
+        s = launch_sparse(ctx, layers[l], cur, B, nullptr, nullptr, masks[l & 1], nullptr, &ny, st);
+        if (s == PF_OK) s = trace_mask(ctx, l, layers[l], masks[l & 1], false, st);
+        if (s != PF_OK) return s;
+        if (l + 1 < n_layers) {
+            float *xn = ctx->xbuf[(l + 1) & 1];
+            if (l + 2 < n_layers)  // its mask takes the buffer layer l has just finished with
+                s = launch_predict(ctx, layers[l + 2], cur, ctx->ypart, ny, xn, B, nullptr, masks[l & 1], st);
+            else
+                s = launch_glue(ctx, cur, ctx->ypart, ny, d, B, xn, st);
+            if (s != PF_OK) return s;
+            cur = xn;
+        }
+    }
+    return launch_glue(ctx, cur, ctx->ypart, ny, d, B, x_out, st);
+}
+
 // Whether a stack can run look-ahead prediction in the two-launch form (k_lookahead.h): fp16
 // weights and the vector path (batch below the matrix-core kernels', at most 3), whole batch
 // staged at once.
@@ -799,10 +834,20 @@ pf_status stack_enqueue_lookahead_merged(pf_ctx *ctx, pf_layer *const *layers, i
 pf_status stack_enqueue(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x, int B,
                         float *x_out, hipStream_t st)
 {
-    if (ctx->lookahead)
-        return ctx->la_merged && la_merged_ok(ctx, layers, n_layers, B)
-                   ? stack_enqueue_lookahead_merged(ctx, layers, n_layers, x, B, x_out, st)
-                   : stack_enqueue_lookahead(ctx, layers, n_layers, x, B, x_out, st);
+    if (ctx->lookahead) {
+        // form 0: two launches per layer where that applies; otherwise (matrix-core batches,
+        // int4) the predictors on a second stream for ReLU layers, where that measured 2 - 14 %
+        // faster than the default schedule (the predictor is the larger share of a two-matrix
+        // layer), and on one stream for gated layers, where the second stream measured 3 - 7 %
+        // slower (FC1 on the matrix cores leaves no room beside it) and one stream costs what
+        // the default schedule costs
+        int form = ctx->la_form;
+        if ((form == 0 || form == 1) && la_merged_ok(ctx, layers, n_layers, B))
+            return stack_enqueue_lookahead_merged(ctx, layers, n_layers, x, B, x_out, st);
+        if (form == 0 || form == 1) form = layers[0]->desc.act == PF_ACT_RELU ? 2 : 3;
+        return form == 2 ? stack_enqueue_lookahead(ctx, layers, n_layers, x, B, x_out, st)
+                         : stack_enqueue_lookahead_serial(ctx, layers, n_layers, x, B, x_out, st);
+    }
     int ny = 1;            // partial sums FC2 left in ctx->ypart
     const float *cur = x;  // input of the layer being enqueued (raw input of the previous one
                            // until the hidden kernel has formed it)
@@ -1392,9 +1437,9 @@ pf_status pf_ctx_set_option(pf_ctx *ctx, int key, int value)
             if (value < 0 || value > pf::kDown2MaxSplit) break;
             ctx->down_split = value;
             return PF_OK;
-        case PF_OPT_LOOKAHEAD_MERGED:
-            if (value < 0 || value > 1) break;
-            ctx->la_merged = value;
+        case PF_OPT_LOOKAHEAD_FORM:
+            if (value < 0 || value > 3) break;
+            ctx->la_form = value;
             return PF_OK;
 
         default:
@@ -1414,7 +1459,7 @@ pf_status pf_ctx_get_option(const pf_ctx *ctx, int key, int *value)
         case PF_OPT_UP_GRID: *value = ctx->up_grid_cap; break;
         case PF_OPT_MFMA_GRID: *value = ctx->mfma_grid; break;
         case PF_OPT_DOWN_SPLIT: *value = ctx->down_split; break;
-        case PF_OPT_LOOKAHEAD_MERGED: *value = ctx->la_merged; break;
+        case PF_OPT_LOOKAHEAD_FORM: *value = ctx->la_form; break;
         default: return PF_EINVAL;
     }
     return PF_OK;

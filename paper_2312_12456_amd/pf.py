@@ -30,7 +30,7 @@ EXPORTS = [
 
 # pf_option keys
 (OPT_FUSED, OPT_SEG_STRIDED, OPT_MFMA_MIN_BATCH, OPT_HIDDEN_MFMA_MIN_ELEMS, OPT_UP_GRID,
- OPT_MFMA_GRID, OPT_DOWN_SPLIT, OPT_LOOKAHEAD_MERGED) = range(8)
+ OPT_MFMA_GRID, OPT_DOWN_SPLIT, OPT_LOOKAHEAD_FORM) = range(8)
 
 
 class PfError(RuntimeError):

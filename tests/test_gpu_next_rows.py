@@ -145,15 +145,16 @@ def test_stack_lookahead_matches_oracle(pf, act, B):
     ctx.set_lookahead(1)
     trace = MaskTrace(ctx, n_layers, cfg.ffn)
     outs = {}
-    for merged in (1, 0):
-        ctx.set_option(pf.OPT_LOOKAHEAD_MERGED, merged)
+    for form in (0, 2, 3):    # automatic, second stream, one stream
+        ctx.set_option(pf.OPT_LOOKAHEAD_FORM, form)
+        merged = form
         out = torch.full_like(x, float("nan"))
         trace.buf.fill_(-1)
         ctx.profile_begin()
         ctx.stack_step(Ls, x, out)
         stats = ctx.profile_end()
         torch.cuda.synchronize()
-        two_launch = merged == 1 and B <= 3
+        two_launch = form == 0 and B <= 3
         assert stats["k_la_up_hidden"][0] == (n_layers if two_launch else 0), stats
         assert stats["k_la_down_out"][0] == (n_layers if two_launch else 0), stats
         check_output(out.cpu().numpy(), ref, "look-ahead stack (merged=%d)" % merged)
@@ -174,7 +175,8 @@ def test_stack_lookahead_matches_oracle(pf, act, B):
         plan.close()
         outs[merged] = out
     # the two forms run the same arithmetic per neuron; FC2's sum has the same order
-    np.testing.assert_allclose(outs[1].cpu().numpy(), outs[0].cpu().numpy(), atol=2e-4, rtol=0)
+    for form in (2, 3):
+        np.testing.assert_allclose(outs[form].cpu().numpy(), outs[0].cpu().numpy(), atol=2e-4, rtol=0)
     ctx.set_mask_trace(None)
     ctx.set_lookahead(0)
     again = torch.empty_like(x)
