@@ -229,7 +229,14 @@ __global__ __launch_bounds__(kDown2I4Threads) void k_down2_i4(
 {
     constexpr int U = (B <= 2) ? 4 : 2;
     __shared__ float red[kDown2I4Waves][B][kDown2I4Cols];
-    const int P = gridDim.y, g = blockIdx.y, tile = blockIdx.x;
+    const int P = gridDim.y, g = blockIdx.y;
+    // Workgroups go to the 8 XCDs round-robin by their linear number, and every XCD has an L2
+    // of its own.  A row's scales (2 bytes per 128 columns, 192 bytes per row at d = 12288) are
+    // shared by all column tiles, so with tile = blockIdx.x every XCD fetched every listed
+    // row's scale lines (measured: FC2 read 1.33 x its algorithmic bytes).  Giving an XCD a
+    // contiguous run of tiles makes it touch one piece of them only.
+    const int nt = gridDim.x;
+    const int tile = (nt % 8 == 0) ? ((int)blockIdx.x % 8) * (nt / 8) + (int)blockIdx.x / 8 : (int)blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cl = lane & 7;                   // which 16 bytes (32 columns) of the row's line
     const int rslot = wave * 8 + (lane >> 3);  // row slot of this lane inside a load
