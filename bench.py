@@ -66,6 +66,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-pred-bias", action="store_true",
                     help="bias-free random predictor (about half of the neurons marked)")
+    ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE",
+                    help="set a library option (pf_ctx_set_option) by its name without the PF_OPT_ "
+                         "prefix, e.g. --opt fused=0 --opt down_split=2 --opt lookahead_form=3")
     ap.add_argument("--seed", type=int, default=2312)
     return ap.parse_args()
 
@@ -358,8 +361,9 @@ def main():
         torch.cuda.synchronize()
         sort_info = {"profiled_tokens": n_prof, "always_on_mean": float(np.mean(prefix))}
 
-    if os.environ.get("PF_X_LA_FORM"):
-        ctx.set_option(pf.OPT_LOOKAHEAD_FORM, int(os.environ["PF_X_LA_FORM"]))
+    for kv in args.opt:
+        key, _, val = kv.partition("=")
+        ctx.set_option(getattr(pf, "OPT_" + key.upper()), int(val))
     ctx.set_lookahead(args.lookahead)
     plan = pf.Plan(ctx, layers, x_buf, out) if args.mode == "graph" else None
 
@@ -381,6 +385,29 @@ def main():
     assert bool(torch.isfinite(out).all()), "non-finite stack output"
     ms_per_step = 1e3 * elapsed / K
     tokens_per_s = B * K / elapsed
+
+    # the same stack with look-ahead prediction (another schedule AND other lists: reported
+    # beside the headline value, never in its place)
+    with_la = None
+    if not args.lookahead and plan is not None and cfg.layers > 1:
+        ctx.set_lookahead(1)
+        plan_la = pf.Plan(ctx, layers, x_buf, out)
+        ctx.set_lookahead(0)
+        for t in range(W):
+            x_buf.copy_(x_all[t % n_tok])
+            plan_la.run()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for t in range(K):
+            x_buf.copy_(x_all[t % n_tok])
+            plan_la.run()
+        torch.cuda.synchronize()
+        e_la = time.perf_counter() - t1
+        plan_la.close()
+        with_la = {"value": round(B * K / e_la, 2), "unit": "tokens/s", "ms_per_step": round(1e3 * e_la / K, 4),
+                   "note": "look-ahead prediction at distance 1: the list of layer l comes from its "
+                           "predictor applied to the input of layer l-1 (an approximation; other lists "
+                           "than the headline run)"}
 
     # per-token latency spread: a second, short run with an event between the steps
     nl = min(K, 128)
@@ -475,7 +502,7 @@ def main():
     # size); an overridden workload has no such summary
     traffic = None
     overridden = (args.rate is not None or args.rank is not None or args.sort_neurons > 0
-                  or args.no_pred_bias or args.lookahead)
+                  or args.no_pred_bias or args.lookahead or args.opt)
     if not overridden:
         try:
             with open(args.traffic_file) as f:
@@ -584,6 +611,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "touched": touched_out,
+        "with_lookahead": with_la,
         "layer": layer,
         "latency": latency,
         "clocks": clocks,

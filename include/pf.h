@@ -209,7 +209,9 @@ pf_status pf_count_activations(pf_ctx *ctx, const pf_layer *layer, uint32_t *cou
  * treated as active in every step WITHOUT being predicted: the predictor's output layer
  * skips their rows (2 r bytes each) and their mask bits and scores read 1.  All internal lists
  * and masks (pf_predict, pf_ctx_last_active, the mask trace) stay in stored numbering;
- * pf_layer_active_original and pf_count_activations translate through the table. */
+ * pf_layer_active_original and pf_count_activations translate through the table.  Takes effect
+ * for the calls made, and the plans created, afterwards.  Errors: PF_EINVAL (null layer,
+ * always_on not a multiple of 64 or outside [0, ffn - 64]). */
 pf_status pf_layer_set_neuron_table(pf_layer *layer, const int32_t *stored_to_original, int always_on);
 
 /* The active set the context used last (as pf_ctx_last_active), in the MODEL's neuron numbering:
