@@ -363,7 +363,7 @@ def main():
 
     for kv in args.opt:
         key, _, val = kv.partition("=")
-        ctx.set_option(int(key) if key.isdigit() else getattr(pf, "OPT_" + key.upper()), int(val))
+        ctx.set_option(getattr(pf, "OPT_" + key.upper()), int(val))
     ctx.set_lookahead(args.lookahead)
     plan = pf.Plan(ctx, layers, x_buf, out) if args.mode == "graph" else None
 
