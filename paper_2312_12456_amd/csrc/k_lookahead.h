@@ -17,6 +17,7 @@
 #include "dev_util.h"
 #include "k_predict.h"
 #include "k_sparse.h"
+#include "k_mfma.h"
 
 namespace pf {
 
@@ -74,6 +75,64 @@ __global__ __launch_bounds__(kDown2Threads) void k_la_down_out(
     } else {
         pred_out_body<B, kLaOutNeurons>(ts, logit_s, out_first ? bid : bid - n_fc2, p2, p_bias, t, r,
                                         ffn_next, thr_logit, nullptr, mask_next, first_word);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// The same two launches for batches on the matrix cores (batch >= 4, or 3 with long rows),
+// from the matrix-core kernels' bodies.  These read the layer input from memory, so a glue
+// kernel of its own runs in front of the first launch.  Ungated layers only: the gated FC1
+// needs 128 KB of LDS per workgroup, which leaves no room for a second role on the CU.
+static_assert(kMfmaThreads == kDown2Threads, "all roles of these launches use 512 threads");
+
+// grid = n_up + n_hid, block = 512: [FC1 of layer l on the matrix cores | hidden layer of
+// predictor l+1 on the matrix cores].  Dynamic LDS: FC1's mask scan + slots (>= the hidden
+// layer's 64 KB of slots).
+template <int ACT>
+__global__ __launch_bounds__(kMfmaThreads) void k_la_up_hidden_mfma(
+    int n_hid, const __half *__restrict__ p1, float *__restrict__ t, int r,
+    const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
+    const float *__restrict__ b_up, const float *__restrict__ x, int B,
+    const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
+    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor)
+{
+    extern __shared__ uint64_t dyn_lds64[];
+    __shared__ uint32_t wave_tot[kMfmaWaves];
+    __shared__ int irow[32];
+    __shared__ float brow[32];
+    __shared__ float logit_s[16][16];
+    const int n_up = (int)gridDim.x - n_hid, bid = (int)blockIdx.x;
+    if (bid < n_up) {  // uniform over the block
+        up_mfma_body<ACT, true>(dyn_lds64, wave_tot, irow, brow, bid, n_up, w_up, w_gate, b_up, x, B,
+                                nullptr, nullptr, mask_words, idx_out, count_out, h, hs, d, ffn, up_floor);
+    } else {
+        rows_mfma_body<8, 512, 0>(dyn_lds64, logit_s, bid - n_up, p1, x, B, d, r, nullptr, 0.f, t, nullptr, 0);
+    }
+}
+
+// grid = tiles * P + (ffn_next - always-on prefix) / 64, block = 512: [FC2 of layer l | output
+// layer of predictor l+1 on the matrix cores].  Dynamic LDS: the output layer's 64 KB of slots;
+// FC2's cross-wave sums live in the same region (a workgroup plays one role), so that two
+// workgroups fit a CU.
+template <int B>
+__global__ __launch_bounds__(kMfmaThreads) void k_la_down_out_mfma(
+    int tiles, int P, const __half *__restrict__ w_down, const float *__restrict__ b_down,
+    const float *__restrict__ h, const int32_t *__restrict__ idx, const int32_t *__restrict__ count_p,
+    float *__restrict__ part, int d, int ffn, const __half *__restrict__ p2,
+    const float *__restrict__ p_bias, const float *__restrict__ t, int r, int ffn_next, float thr_logit,
+    uint64_t *__restrict__ mask_next, int first_word)
+{
+    extern __shared__ uint64_t dyn_lds64[];
+    __shared__ float logit_s[16][64];
+    static_assert(sizeof(float) * kDown2Waves * B * kDown2Cols <= (size_t)kMfmaWaves * kRowsMfmaSlotBytes,
+                  "FC2's sums fit the slots");
+    const int bid = (int)blockIdx.x, n_fc2 = tiles * P;
+    if (bid < n_fc2) {  // uniform over the block
+        down2_body<B>(reinterpret_cast<float(*)[B][kDown2Cols]>(dyn_lds64), bid % tiles, bid / tiles, P, w_down,
+                      b_down, h, idx, count_p, part, d, ffn);
+    } else {
+        rows_mfma_body<64, 64, 1>(dyn_lds64, logit_s, bid - n_fc2, p2, t, B, r, ffn_next, p_bias, thr_logit,
+                                  nullptr, mask_next, first_word);
     }
 }
 

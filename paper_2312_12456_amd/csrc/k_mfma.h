@@ -247,18 +247,21 @@ __device__ __forceinline__ void up_mfma_passes(const UpMfmaArgs &a)
 // with 128-element chunks.  The 8 waves of a block take the chunks round-robin (wave w:
 // chunks w, w + 8, ...) for the same rows and their C tiles are added in LDS in wave order.
 // d % 32 == 0, B <= 16.
+// The body takes its block number and the number of blocks of its role explicitly, so that a
+// launch can run it in a range of its blocks beside another role.  Its pointer parameters carry
+// no restrict qualifier on purpose: a wave reads back from LDS what its own global -> LDS loads
+// wrote, and the wait between the two is the compiler's, which places it only while it takes
+// the two accesses to alias.  Inlining a function with restrict parameters tags its accesses
+// with no-alias scopes, and with those the waits were dropped (wrong sums on the device).
 template <int ACT, bool FROM_MASK>
-__global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
-    const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
-    const float *__restrict__ b_up, const float *__restrict__ x, int B,
-    const int32_t *__restrict__ idx_in, const int32_t *__restrict__ count_in,
-    const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
-    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor)
+__device__ __forceinline__ void up_mfma_body(
+    uint64_t *dyn_lds64, uint32_t *wave_tot, int *irow, float *brow, const int bid, const int nblocks,
+    const __half *w_up, const __half *w_gate,
+    const float *b_up, const float *x, int B,
+    const int32_t *idx_in, const int32_t *count_in,
+    const uint64_t *mask_words, int32_t *idx_out,
+    int32_t *count_out, float *h, int hs, int d, int ffn, float up_floor)
 {
-    extern __shared__ uint64_t dyn_lds64[];
-    __shared__ uint32_t wave_tot[kMfmaWaves];
-    __shared__ int irow[32];
-    __shared__ float brow[32];
     constexpr bool GATED = (ACT == 1);
     const int nwords = ffn / 64;
     uint64_t *words_lds = dyn_lds64;
@@ -271,7 +274,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     int top_step = 1;
     if (FROM_MASK) {
         n = (int)mask_prefix<kMfmaThreads>(mask_words, nwords, words_lds, pre_lds, wave_tot);
-        if (blockIdx.x == 0 && threadIdx.x == 0) *count_out = n;
+        if (bid == 0 && threadIdx.x == 0) *count_out = n;
         while (top_step * 2 < nwords) top_step *= 2;
     } else {
         n = min(max(*count_in, 0), ffn);
@@ -297,8 +300,8 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     a.nwords = nwords;
     a.top_step = top_step;
     a.up_floor = up_floor;
-    const int rpb = (n + (int)gridDim.x - 1) / (int)gridDim.x;
-    a.j_begin = min(n, (int)blockIdx.x * rpb);
+    const int rpb = (n + nblocks - 1) / nblocks;
+    a.j_begin = min(n, bid * rpb);
     a.j_end = min(n, a.j_begin + rpb);
     PF_TSTAMP(2, 1);
     if (rpb <= 16)
@@ -306,6 +309,23 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     else
         up_mfma_passes<32, ACT, FROM_MASK>(a);
     PF_TSTAMP(2, 5);
+}
+
+template <int ACT, bool FROM_MASK>
+__global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
+    const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
+    const float *__restrict__ b_up, const float *__restrict__ x, int B,
+    const int32_t *__restrict__ idx_in, const int32_t *__restrict__ count_in,
+    const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
+    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor)
+{
+    extern __shared__ uint64_t dyn_lds64[];
+    __shared__ uint32_t wave_tot[kMfmaWaves];
+    __shared__ int irow[32];
+    __shared__ float brow[32];
+    up_mfma_body<ACT, FROM_MASK>(dyn_lds64, wave_tot, irow, brow, (int)blockIdx.x, (int)gridDim.x, w_up, w_gate,
+                                 b_up, x, B, idx_in, count_in, mask_words, idx_out, count_out, h, hs, d,
+                                 ffn, up_floor);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -341,24 +361,16 @@ __device__ __forceinline__ void rows_mfma_issue(rsrc_t w, char *slot, uint32_t r
     }
 }
 
+// Body: bid0 = the block's number within its role, logit_s = [16][16 * tiles] floats of LDS.
+// No restrict qualifiers, for the same reason as in up_mfma_body.
 template <int R, int KC, int EPI>
-__global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
-    const __half *__restrict__ w, const float *__restrict__ v, int B, int K, int nrows,
-    const float *__restrict__ p_bias, float thr_logit, float *__restrict__ out,
-    uint64_t *__restrict__ mask_words, int first_word, const int32_t *__restrict__ skip)
+__device__ __forceinline__ void rows_mfma_body(
+    uint64_t *dyn_lds64, float (*logit_s)[16 * ((R + 15) / 16)], const int bid0,
+    const __half *w, const float *v, int B, int K, int nrows,
+    const float *p_bias, float thr_logit, float *out,
+    uint64_t *mask_words, int first_word)
 {
-    extern __shared__ uint64_t dyn_lds64[];
     constexpr int T = (R + 15) / 16;  // MFMA tiles per block
-    // adaptive layer step: a set flag means this step runs dense (no prediction; all marked)
-    if (skip != nullptr && *skip != 0) {
-        if (EPI == 1) {
-            if (threadIdx.x == 0) mask_words[first_word + (int)blockIdx.x] = ~0ull;
-            if (blockIdx.x == 0)
-                for (int w = threadIdx.x; w < first_word; w += kMfmaThreads) mask_words[w] = ~0ull;
-        }
-        return;
-    }
-    __shared__ float logit_s[16][16 * T];
     static_assert(R * KC * 2 == kRowsMfmaSlotBytes, "slot size");
     static_assert(EPI == 0 || R == 64, "the output layer writes one mask word per block");
     constexpr int STEPS = KC / 32;                // MFMA K steps per chunk
@@ -368,10 +380,10 @@ __global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
     char *slots = reinterpret_cast<char *>(dyn_lds64);
     char *slot = slots + (size_t)wave * kRowsMfmaSlotBytes;
     // EPI 1: the launch covers the rows from 64 * first_word on (always-on prefix skipped)
-    const int blk = (int)blockIdx.x + (EPI == 1 ? first_word : 0);
+    const int blk = bid0 + (EPI == 1 ? first_word : 0);
     const int r0 = blk * R;
     const int nleft = nrows - r0;  // rows of this block that exist (>= 1)
-    if (EPI == 1 && blockIdx.x == 0 && first_word > 0) {
+    if (EPI == 1 && bid0 == 0 && first_word > 0) {
         for (int w = threadIdx.x; w < first_word; w += kMfmaThreads) mask_words[w] = ~0ull;
         if (out != nullptr)
             for (int e = threadIdx.x; e < B * first_word * 64; e += kMfmaThreads)
@@ -481,6 +493,28 @@ __global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
         }
     }
     PF_TSTAMP(EPI, 2);
+}
+
+template <int R, int KC, int EPI>
+__global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
+    const __half *__restrict__ w, const float *__restrict__ v, int B, int K, int nrows,
+    const float *__restrict__ p_bias, float thr_logit, float *__restrict__ out,
+    uint64_t *__restrict__ mask_words, int first_word, const int32_t *__restrict__ skip)
+{
+    extern __shared__ uint64_t dyn_lds64[];
+    constexpr int T = (R + 15) / 16;
+    __shared__ float logit_s[16][16 * T];
+    // adaptive layer step: a set flag means this step runs dense (no prediction; all marked)
+    if (skip != nullptr && *skip != 0) {
+        if (EPI == 1) {
+            if (threadIdx.x == 0) mask_words[first_word + (int)blockIdx.x] = ~0ull;
+            if (blockIdx.x == 0)
+                for (int w = threadIdx.x; w < first_word; w += kMfmaThreads) mask_words[w] = ~0ull;
+        }
+        return;
+    }
+    rows_mfma_body<R, KC, EPI>(dyn_lds64, logit_s, (int)blockIdx.x, w, v, B, K, nrows, p_bias, thr_logit,
+                               out, mask_words, first_word);
 }
 
 }  // namespace pf

@@ -33,6 +33,7 @@ enum KernelId {
     K_PRED_HIDDEN = 0, K_PRED_OUT, K_COMPACT, K_UP, K_DOWN, K_GLUE, K_UP_MFMA, K_COMBINE, K_OUT_UP,
     K_DOWN_MASK, K_LA_UP_HIDDEN, K_LA_DOWN_OUT, K_NUM
 };
+static_assert(K_NUM <= 16, "pf_profile_end documents a capacity of 16 entries");
 const char *const kKernelNames[K_NUM] = {"k_pred_hidden", "k_pred_out", "k_compact", "k_up",
                                          "k_down",        "k_glue",     "k_up_mfma",  "k_combine",
                                          "k_out_up",      "k_down_mask", "k_la_up_hidden",
@@ -209,6 +210,13 @@ hipError_t allow_lds_mfma()
     if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, true>);
     if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<8, 512, 0>);
     if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<64, 64, 1>);
+    if (e == hipSuccess) e = allow_lds(pf::k_la_up_hidden_mfma<0>);
+    if (e == hipSuccess) e = allow_lds(pf::k_la_down_out_mfma<3>);
+    if (e == hipSuccess) e = allow_lds(pf::k_la_down_out_mfma<4>);
+    if (e == hipSuccess) e = allow_lds(pf::k_la_down_out_mfma<5>);
+    if (e == hipSuccess) e = allow_lds(pf::k_la_down_out_mfma<6>);
+    if (e == hipSuccess) e = allow_lds(pf::k_la_down_out_mfma<7>);
+    if (e == hipSuccess) e = allow_lds(pf::k_la_down_out_mfma<8>);
     return e;
 }
 
@@ -831,6 +839,90 @@ pf_status stack_enqueue_lookahead_merged(pf_ctx *ctx, pf_layer *const *layers, i
     return launch_glue(ctx, cur, ctx->ypart, ny, d, B, x_out, st);
 }
 
+// Whether a stack can run look-ahead prediction in the two-launch form of the matrix-core
+// kernels: ungated fp16 layers whose FC1 and predictor run on the matrix cores at this batch.
+bool la_merged_mfma_ok(const pf_ctx *ctx, pf_layer *const *layers, int n_layers, int B)
+{
+    if (B < 3 || ctx->lds_budget <= kLdsDefault) return false;
+    for (int l = 0; l < n_layers; ++l) {
+        const pf_layer_desc &D = layers[l]->desc;
+        if (D.wtype != PF_W_FP16 || D.act != PF_ACT_RELU || B < mfma_from(ctx, D)) return false;
+        if (D.d % 32 != 0 || D.r % 32 != 0) return false;
+        if (pf::up_mfma_lds_bytes(D.ffn, true, false) > (size_t)ctx->lds_budget) return false;
+    }
+    return true;
+}
+
+// One decode step with look-ahead prediction on the matrix cores: glue, then [FC1 of layer l |
+// hidden layer of predictor l+1], then [FC2 of layer l | output layer of predictor l+1].
+pf_status stack_enqueue_lookahead_merged_mfma(pf_ctx *ctx, pf_layer *const *layers, int n_layers,
+                                              const float *x, int B, float *x_out, hipStream_t st)
+{
+    uint64_t *masks[2] = {ctx->mask_words, ctx->mask_words2};
+    const int d = layers[0]->desc.d;
+    pf_status s = launch_predict(ctx, layers[0], x, nullptr, 0, nullptr, B, nullptr, masks[0], st);
+    if (s != PF_OK) return s;
+    int ny = 1;
+    const float *cur = x;
+    const size_t slots = (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes;
+    for (int l = 0; l < n_layers; ++l) {
+        const pf_layer *L = layers[l];
+        const pf_layer *N = l + 1 < n_layers ? layers[l + 1] : nullptr;
+        const pf_layer_desc &D = L->desc;
+        if (l > 0) {  // the matrix-core kernels read the layer input from memory
+            float *xn = ctx->xbuf[l & 1];
+            s = launch_glue(ctx, cur, ctx->ypart, ny, d, B, xn, st);
+            if (s != PF_OK) return s;
+            cur = xn;
+        }
+        const int n_hid = N ? cdiv(N->desc.r, 8) : 0;
+        const int n_up = ctx->mfma_grid > 0 ? ctx->mfma_grid : ctx->num_cu;
+        size_t lds1 = pf::up_mfma_lds_bytes(D.ffn, true, false);
+        if (lds1 < slots) lds1 = slots;
+        {
+            ProfScope ps(ctx, K_LA_UP_HIDDEN);
+            PF_LAUNCH(ps, (pf::k_la_up_hidden_mfma<0>), dim3(n_up + n_hid), dim3(pf::kMfmaThreads), lds1, st,
+                      n_hid, static_cast<const __half *>(N ? N->w.p1 : nullptr), ctx->t, N ? N->desc.r : 0,
+                      static_cast<const __half *>(L->w.w_up), static_cast<const __half *>(L->w.w_gate),
+                      L->w.b_up, cur, B, (const uint64_t *)masks[l & 1], ctx->idx, ctx->count, ctx->h,
+                      pf::h_stride(B), D.d, D.ffn, up_floor_of(D));
+        }
+        ctx->last_mask = masks[l & 1];
+        ctx->last_idx = ctx->idx;
+        ctx->last_count = ctx->count;
+        const int tiles = cdiv(D.d, pf::kDown2Cols);
+        int P = ctx->down_split > 0 ? ctx->down_split : ctx->num_cu / tiles;
+        if (P < 1) P = 1;
+        if (P > pf::kDown2MaxSplit) P = pf::kDown2MaxSplit;
+        const int n_out = N ? (N->desc.ffn - N->always_on) / 64 : 0;
+        {
+            ProfScope ps(ctx, K_LA_DOWN_OUT);
+#define PF_LA2M(BB)                                                                               \
+    PF_LAUNCH(ps, (pf::k_la_down_out_mfma<BB>), dim3(tiles * P + n_out), dim3(pf::kMfmaThreads), slots, \
+              st, tiles, P, static_cast<const __half *>(L->w.w_down), L->w.b_down,                \
+              (const float *)ctx->h, (const int32_t *)ctx->idx, (const int32_t *)ctx->count,      \
+              ctx->ypart, D.d, D.ffn, static_cast<const __half *>(N ? N->w.p2 : nullptr),         \
+              N ? N->w.p_bias : nullptr, (const float *)ctx->t, N ? N->desc.r : 0,                \
+              N ? N->desc.ffn : 0, N ? N->thr_logit : 0.f, masks[(l + 1) & 1],                    \
+              N ? N->always_on / 64 : 0)
+            switch (B) {
+                case 3: PF_LA2M(3); break;
+                case 4: PF_LA2M(4); break;
+                case 5: PF_LA2M(5); break;
+                case 6: PF_LA2M(6); break;
+                case 7: PF_LA2M(7); break;
+                default: PF_LA2M(8); break;
+            }
+#undef PF_LA2M
+        }
+        ny = P;
+        PF_HIP(ctx, hipGetLastError());
+        s = trace_mask(ctx, l, L, masks[l & 1], false, st);
+        if (s != PF_OK) return s;
+    }
+    return launch_glue(ctx, cur, ctx->ypart, ny, d, B, x_out, st);
+}
+
 pf_status stack_enqueue(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x, int B,
                         float *x_out, hipStream_t st)
 {
@@ -844,6 +936,8 @@ pf_status stack_enqueue(pf_ctx *ctx, pf_layer *const *layers, int n_layers, cons
         int form = ctx->la_form;
         if ((form == 0 || form == 1) && la_merged_ok(ctx, layers, n_layers, B))
             return stack_enqueue_lookahead_merged(ctx, layers, n_layers, x, B, x_out, st);
+        if ((form == 0 || form == 1) && la_merged_mfma_ok(ctx, layers, n_layers, B))
+            return stack_enqueue_lookahead_merged_mfma(ctx, layers, n_layers, x, B, x_out, st);
         if (form == 0 || form == 1) form = layers[0]->desc.act == PF_ACT_RELU ? 2 : 3;
         return form == 2 ? stack_enqueue_lookahead(ctx, layers, n_layers, x, B, x_out, st)
                          : stack_enqueue_lookahead_serial(ctx, layers, n_layers, x, B, x_out, st);
