@@ -81,8 +81,9 @@ __global__ __launch_bounds__(kDown2Threads) void k_la_down_out(
 // ---------------------------------------------------------------------------------------
 // The same two launches for batches on the matrix cores (batch >= 4, or 3 with long rows),
 // from the matrix-core kernels' bodies.  These read the layer input from memory, so a glue
-// kernel of its own runs in front of the first launch.  Ungated layers only: the gated FC1
-// needs 128 KB of LDS per workgroup, which leaves no room for a second role on the CU.
+// kernel of its own runs in front of the first launch.  Ungated layers: two workgroups of
+// either role fit a CU.  The gated FC1 needs 128 KB of LDS per workgroup, so there a CU holds
+// one workgroup at a time and the hidden-layer role follows FC1 rather than sharing the CUs.
 static_assert(kMfmaThreads == kDown2Threads, "all roles of these launches use 512 threads");
 
 // grid = n_up + n_hid, block = 512: [FC1 of layer l on the matrix cores | hidden layer of

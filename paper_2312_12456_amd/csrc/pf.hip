@@ -211,6 +211,7 @@ hipError_t allow_lds_mfma()
     if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<8, 512, 0>);
     if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<64, 64, 1>);
     if (e == hipSuccess) e = allow_lds(pf::k_la_up_hidden_mfma<0>);
+    if (e == hipSuccess) e = allow_lds(pf::k_la_up_hidden_mfma<1>);
     if (e == hipSuccess) e = allow_lds(pf::k_la_down_out_mfma<3>);
     if (e == hipSuccess) e = allow_lds(pf::k_la_down_out_mfma<4>);
     if (e == hipSuccess) e = allow_lds(pf::k_la_down_out_mfma<5>);
@@ -840,15 +841,17 @@ pf_status stack_enqueue_lookahead_merged(pf_ctx *ctx, pf_layer *const *layers, i
 }
 
 // Whether a stack can run look-ahead prediction in the two-launch form of the matrix-core
-// kernels: ungated fp16 layers whose FC1 and predictor run on the matrix cores at this batch.
+// kernels: fp16 layers whose FC1 and predictor run on the matrix cores at this batch.  (Gated
+// layers take the whole LDS of a CU per FC1 workgroup: the hidden-layer role then follows FC1
+// on the CUs instead of sharing them, and still saves the launch boundary.)
 bool la_merged_mfma_ok(const pf_ctx *ctx, pf_layer *const *layers, int n_layers, int B)
 {
     if (B < 3 || ctx->lds_budget <= kLdsDefault) return false;
     for (int l = 0; l < n_layers; ++l) {
         const pf_layer_desc &D = layers[l]->desc;
-        if (D.wtype != PF_W_FP16 || D.act != PF_ACT_RELU || B < mfma_from(ctx, D)) return false;
+        if (D.wtype != PF_W_FP16 || B < mfma_from(ctx, D)) return false;
         if (D.d % 32 != 0 || D.r % 32 != 0) return false;
-        if (pf::up_mfma_lds_bytes(D.ffn, true, false) > (size_t)ctx->lds_budget) return false;
+        if (pf::up_mfma_lds_bytes(D.ffn, true, D.act != PF_ACT_RELU) > (size_t)ctx->lds_budget) return false;
     }
     return true;
 }
@@ -877,15 +880,22 @@ pf_status stack_enqueue_lookahead_merged_mfma(pf_ctx *ctx, pf_layer *const *laye
         }
         const int n_hid = N ? cdiv(N->desc.r, 8) : 0;
         const int n_up = ctx->mfma_grid > 0 ? ctx->mfma_grid : ctx->num_cu;
-        size_t lds1 = pf::up_mfma_lds_bytes(D.ffn, true, false);
+        const bool gated = D.act != PF_ACT_RELU;
+        size_t lds1 = pf::up_mfma_lds_bytes(D.ffn, true, gated);
         if (lds1 < slots) lds1 = slots;
         {
             ProfScope ps(ctx, K_LA_UP_HIDDEN);
-            PF_LAUNCH(ps, (pf::k_la_up_hidden_mfma<0>), dim3(n_up + n_hid), dim3(pf::kMfmaThreads), lds1, st,
-                      n_hid, static_cast<const __half *>(N ? N->w.p1 : nullptr), ctx->t, N ? N->desc.r : 0,
-                      static_cast<const __half *>(L->w.w_up), static_cast<const __half *>(L->w.w_gate),
-                      L->w.b_up, cur, B, (const uint64_t *)masks[l & 1], ctx->idx, ctx->count, ctx->h,
-                      pf::h_stride(B), D.d, D.ffn, up_floor_of(D));
+#define PF_LA1M(ACT)                                                                                   \
+    PF_LAUNCH(ps, (pf::k_la_up_hidden_mfma<ACT>), dim3(n_up + n_hid), dim3(pf::kMfmaThreads), lds1, st, \
+              n_hid, static_cast<const __half *>(N ? N->w.p1 : nullptr), ctx->t, N ? N->desc.r : 0,    \
+              static_cast<const __half *>(L->w.w_up), static_cast<const __half *>(L->w.w_gate),        \
+              L->w.b_up, cur, B, (const uint64_t *)masks[l & 1], ctx->idx, ctx->count, ctx->h,         \
+              pf::h_stride(B), D.d, D.ffn, up_floor_of(D))
+            if (gated)
+                PF_LA1M(1);
+            else
+                PF_LA1M(0);
+#undef PF_LA1M
         }
         ctx->last_mask = masks[l & 1];
         ctx->last_idx = ctx->idx;

@@ -114,10 +114,11 @@ def test_stack_lookahead_matches_oracle(pf, act, B):
 
 
 @pytest.mark.parametrize("B", [4, 5, 8])
-def test_stack_lookahead_on_matrix_cores_matches_oracle(pf, B):
-    """The two-launch form built from the matrix-core kernels (ungated fp16 layers, rows and
-    predictor rank multiples of 32, batch on the matrix cores)."""
-    _lookahead_case(pf, wl.ACT_RELU, B, d=512, r=128, two_launch=True)
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU, wl.ACT_DRELU])
+def test_stack_lookahead_on_matrix_cores_matches_oracle(pf, act, B):
+    """The two-launch form built from the matrix-core kernels (fp16 layers, rows and predictor
+    rank multiples of 32, batch on the matrix cores)."""
+    _lookahead_case(pf, act, B, d=512, r=128, two_launch=True)
 
 
 def _lookahead_case(pf, act, B, d, r, two_launch):
