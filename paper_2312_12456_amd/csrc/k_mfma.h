@@ -128,11 +128,16 @@ __device__ __forceinline__ void up_mfma_passes(const UpMfmaArgs &a)
                 if ((unsigned)ir[t] >= (unsigned)a.ffn) ir[t] = -1;
             }
         }
+        // the rows' biases are fetched here and parked in LDS only after the chunk loop, so that
+        // wave 0 does not wait for them before it puts its first chunk in flight
+        float bpre[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) bpre[t] = 0.f;
         if (wave == 0 && kg == 0) {
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 a.irow[16 * t + row16] = ir[t];
-                a.brow[16 * t + row16] = (a.b_up != nullptr && ir[t] >= 0) ? a.b_up[ir[t]] : 0.f;
+                if (a.b_up != nullptr && ir[t] >= 0) bpre[t] = a.b_up[ir[t]];
                 if (FROM_MASK && ir[t] >= 0) a.idx_out[jr[t]] = ir[t];
             }
         }
@@ -211,6 +216,10 @@ __device__ __forceinline__ void up_mfma_passes(const UpMfmaArgs &a)
         // this lane holds C[row 4*kg + e][col row16] of its chunks, per tile; the wave's slot
         // is free now: [tile][up | gate][256]
         float *ctile = reinterpret_cast<float *>(slot);
+        if (wave == 0 && kg == 0) {
+#pragma unroll
+            for (int t = 0; t < T; ++t) a.brow[16 * t + row16] = bpre[t];
+        }
 #pragma unroll
         for (int t = 0; t < T; ++t)
 #pragma unroll
@@ -418,6 +427,16 @@ __device__ __forceinline__ void rows_mfma_body(
         rows_mfma_issue<R, KC>(wr, slot, row0_off, row_bytes, nleft, c, K, lane);
         load_x(c, 0, xa[0], xb[0]);
     }
+    // output layer: the biases of the rows this thread finishes, fetched behind the first chunk
+    // (read only after the chunk loop: their latency is off the block's tail)
+    constexpr int NE = (T * 256 + kMfmaThreads - 1) / kMfmaThreads;
+    float bias_pre[NE];
+#pragma unroll
+    for (int i = 0; i < NE; ++i) {
+        const int e = (int)threadIdx.x + i * kMfmaThreads;
+        const int row = (e >> 8) * 16 + ((e >> 4) & 15);
+        bias_pre[i] = (EPI == 1 && p_bias != nullptr && e < T * 256) ? p_bias[r0 + row] : 0.f;
+    }
     while (c < nchunks) {  // wave-uniform
         const int cn = c + kMfmaWaves;
 #pragma unroll
@@ -469,7 +488,10 @@ __device__ __forceinline__ void rows_mfma_body(
 #pragma unroll
         for (int e = 0; e < 4; ++e) ctile[t * 256 + (kg * 4 + e) * 16 + row16] = acc[t][e];
     __syncthreads();
-    for (int e = threadIdx.x; e < T * 256; e += kMfmaThreads) {
+#pragma unroll
+    for (int i = 0; i < NE; ++i) {
+        const int e = (int)threadIdx.x + i * kMfmaThreads;
+        if (e >= T * 256) break;
         const int row = (e >> 8) * 16 + ((e >> 4) & 15), col = e & 15;
         float sum = 0.f;
 #pragma unroll
@@ -478,7 +500,7 @@ __device__ __forceinline__ void rows_mfma_body(
         if (EPI == 0) {
             if (col < B && row < R && row < nleft) out[(size_t)col * nrows + r0 + row] = fmaxf(sum, 0.f);
         } else {
-            const float lg = sum + (p_bias ? p_bias[r0 + row] : 0.f);
+            const float lg = sum + bias_pre[i];
             logit_s[col][row] = lg;
             if (out != nullptr && col < B) out[(size_t)col * nrows + r0 + row] = 1.f / (1.f + __expf(-lg));
         }
