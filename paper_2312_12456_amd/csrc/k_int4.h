@@ -109,8 +109,11 @@ constexpr int kUpI4Waves = kUpI4Threads / kWave;
 
 // FC1 (and gate) over listed neurons, int4 weights: the structure of k_up with 2048-element
 // chunks.  With FROM_MASK the list is derived from the mask words inside the kernel.
+// The body takes its block number and the number of blocks of its role explicitly, so that a
+// launch can run it in a range of its blocks beside another role.
 template <int B, int ACT, bool FROM_MASK>
-__global__ __launch_bounds__(kUpI4Threads) void k_up_i4(
+__device__ __forceinline__ void up_i4_body(
+    float *xs, uint32_t *wave_tot, const int bid, const int nblocks,
     const uint8_t *__restrict__ q_up, const __half *__restrict__ s_up,
     const uint8_t *__restrict__ q_gate, const __half *__restrict__ s_gate,
     const float *__restrict__ b_up, const float *__restrict__ x,
@@ -118,14 +121,12 @@ __global__ __launch_bounds__(kUpI4Threads) void k_up_i4(
     const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
     int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor)
 {
-    extern __shared__ float xs[];
-    __shared__ uint32_t wave_tot[kUpI4Waves];
     constexpr int U = 2;
     constexpr bool GATED = (ACT == 1);
     const int lane = threadIdx.x & 63;
     const int wave = wave_uniform(threadIdx.x >> 6);
     const int nch = (d + kI4Chunk - 1) / kI4Chunk, kpad = nch * kI4Chunk;
-    const int stride = gridDim.x * kUpI4Waves;
+    const int stride = nblocks * kUpI4Waves;
     const int nwords = ffn / 64;
     uint64_t *words_lds = reinterpret_cast<uint64_t *>(xs + (size_t)B * kpad + kStageScrap);
     uint32_t *pre_lds = reinterpret_cast<uint32_t *>(words_lds + nwords);
@@ -136,11 +137,11 @@ __global__ __launch_bounds__(kUpI4Threads) void k_up_i4(
     int n;
     if (FROM_MASK) {
         n = (int)mask_prefix<kUpI4Threads>(mask_words, nwords, words_lds, pre_lds, wave_tot);
-        if (blockIdx.x == 0 && threadIdx.x == 0) *count_out = n;
+        if (bid == 0 && threadIdx.x == 0) *count_out = n;
     } else {
         n = min(max(*count_in, 0), ffn);
     }
-    if ((int)blockIdx.x * kUpI4Waves >= n) return;  // uniform over the block
+    if (bid * kUpI4Waves >= n) return;  // uniform over the block
 
     auto neuron_of = [&](int j) -> int {
         if (FROM_MASK) {
@@ -151,7 +152,7 @@ __global__ __launch_bounds__(kUpI4Threads) void k_up_i4(
         return idx_in[j];
     };
 
-    int j = blockIdx.x * kUpI4Waves + wave;
+    int j = bid * kUpI4Waves + wave;
     int i = 0;
     bool valid = false;
     if (j < n) {
@@ -208,6 +209,21 @@ __global__ __launch_bounds__(kUpI4Threads) void k_up_i4(
     }
 }
 
+template <int B, int ACT, bool FROM_MASK>
+__global__ __launch_bounds__(kUpI4Threads) void k_up_i4(
+    const uint8_t *__restrict__ q_up, const __half *__restrict__ s_up,
+    const uint8_t *__restrict__ q_gate, const __half *__restrict__ s_gate,
+    const float *__restrict__ b_up, const float *__restrict__ x,
+    const int32_t *__restrict__ idx_in, const int32_t *__restrict__ count_in,
+    const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
+    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor)
+{
+    extern __shared__ float xs[];
+    __shared__ uint32_t wave_tot[kUpI4Waves];
+    up_i4_body<B, ACT, FROM_MASK>(xs, wave_tot, (int)blockIdx.x, (int)gridDim.x, q_up, s_up, q_gate, s_gate, b_up,
+                                  x, idx_in, count_in, mask_words, idx_out, count_out, h, hs, d, ffn, up_floor);
+}
+
 // ---------------------------------------------------------------------------------------
 // FC2 over listed neurons, int4 weights, row-split like k_down2: a workgroup owns 256 output
 // columns = one full 128-byte line of nibbles per row (8 lanes x 16 bytes, 32 columns per
@@ -220,23 +236,22 @@ constexpr int kDown2I4Waves = kDown2I4Threads / kWave;
 constexpr int kDown2I4Cols = 256;
 constexpr int kDown2I4RowsPerLoad = kDown2I4Threads / 8;
 
+// Body: bx = the block's number among the nt column tiles of row group g (of P).
 template <int B>
-__global__ __launch_bounds__(kDown2I4Threads) void k_down2_i4(
+__device__ __forceinline__ void down2_i4_body(
+    float (*red)[B][kDown2I4Cols], const int bx, const int nt, const int g, const int P,
     const uint8_t *__restrict__ q_down, const __half *__restrict__ s_down,
     const float *__restrict__ b_down, const float *__restrict__ h,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ count_p, float *__restrict__ part,
     int d, int ffn)
 {
     constexpr int U = (B <= 2) ? 4 : 2;
-    __shared__ float red[kDown2I4Waves][B][kDown2I4Cols];
-    const int P = gridDim.y, g = blockIdx.y;
     // Workgroups go to the 8 XCDs round-robin by their linear number, and every XCD has an L2
     // of its own.  A row's scales (2 bytes per 128 columns, 192 bytes per row at d = 12288) are
     // shared by all column tiles, so with tile = blockIdx.x every XCD fetched every listed
     // row's scale lines (measured: FC2 read 1.33 x its algorithmic bytes).  Giving an XCD a
     // contiguous run of tiles makes it touch one piece of them only.
-    const int nt = gridDim.x;
-    const int tile = (nt % 8 == 0) ? ((int)blockIdx.x % 8) * (nt / 8) + (int)blockIdx.x / 8 : (int)blockIdx.x;
+    const int tile = (nt % 8 == 0) ? (bx % 8) * (nt / 8) + bx / 8 : bx;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cl = lane & 7;                   // which 16 bytes (32 columns) of the row's line
     const int rslot = wave * 8 + (lane >> 3);  // row slot of this lane inside a load
@@ -334,6 +349,18 @@ __global__ __launch_bounds__(kDown2I4Threads) void k_down2_i4(
         }
     }
     PF_TSTAMP(3, 5);
+}
+
+template <int B>
+__global__ __launch_bounds__(kDown2I4Threads) void k_down2_i4(
+    const uint8_t *__restrict__ q_down, const __half *__restrict__ s_down,
+    const float *__restrict__ b_down, const float *__restrict__ h,
+    const int32_t *__restrict__ idx, const int32_t *__restrict__ count_p, float *__restrict__ part,
+    int d, int ffn)
+{
+    __shared__ float red[kDown2I4Waves][B][kDown2I4Cols];
+    down2_i4_body<B>(red, (int)blockIdx.x, (int)gridDim.x, (int)blockIdx.y, (int)gridDim.y, q_down, s_down,
+                     b_down, h, idx, count_p, part, d, ffn);
 }
 
 }  // namespace pf

@@ -18,6 +18,7 @@
 #include "k_predict.h"
 #include "k_sparse.h"
 #include "k_mfma.h"
+#include "k_int4.h"
 
 namespace pf {
 
@@ -134,6 +135,59 @@ __global__ __launch_bounds__(kMfmaThreads) void k_la_down_out_mfma(
     } else {
         rows_mfma_body<64, 64, 1>(dyn_lds64, logit_s, bid - n_fc2, p2, t, B, r, ffn_next, p_bias, thr_logit,
                                   nullptr, mask_next, first_word);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// The same two launches over int4 weights (the predictor stays fp16).  FC1's int4 kernel reads
+// the layer input from memory, so a glue kernel of its own runs in front of the first launch.
+static_assert(kUpI4Threads == kDown2I4Threads && kDown2I4Threads == kDown2Threads, "512 threads in all roles");
+
+// grid = n_up + n_hid, block = 512: [FC1 of layer l over int4 rows | hidden layer of predictor
+// l+1, 8 rows per block].  Dynamic LDS: FC1's staged input + scrap + mask scan (>= the hidden
+// layer's staged input).
+template <int B, int ACT>
+__global__ __launch_bounds__(kUpI4Threads) void k_la_up_hidden_i4(
+    int n_hid, const __half *__restrict__ p1, float *__restrict__ t, int r,
+    const uint8_t *__restrict__ q_up, const __half *__restrict__ s_up,
+    const uint8_t *__restrict__ q_gate, const __half *__restrict__ s_gate,
+    const float *__restrict__ b_up, const float *__restrict__ x,
+    const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
+    int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor)
+{
+    extern __shared__ float xs[];
+    __shared__ uint32_t wave_tot[kUpI4Waves];
+    __shared__ float ss_w[kUpI4Waves][B];
+    const int n_up = (int)gridDim.x - n_hid, bid = (int)blockIdx.x;
+    if (bid < n_up) {  // uniform over the block
+        up_i4_body<B, ACT, true>(xs, wave_tot, bid, n_up, q_up, s_up, q_gate, s_gate, b_up, x, nullptr, nullptr,
+                                 mask_words, idx_out, count_out, h, hs, d, ffn, up_floor);
+    } else {
+        pred_hidden_body<B, false, 1, kUpI4Threads>(xs, ss_w, bid - n_up, false, p1, x, nullptr, 0, 0, nullptr, t,
+                                                    d, r, 0);
+    }
+}
+
+// grid = tiles * P + (ffn_next - always-on prefix) / 32, block = 512: [FC2 of layer l over int4
+// rows | output layer of predictor l+1].  Dynamic LDS: staged hidden vector [B][rpad].
+template <int B>
+__global__ __launch_bounds__(kDown2I4Threads) void k_la_down_out_i4(
+    int tiles, int P, const uint8_t *__restrict__ q_down, const __half *__restrict__ s_down,
+    const float *__restrict__ b_down, const float *__restrict__ h, const int32_t *__restrict__ idx,
+    const int32_t *__restrict__ count_p, float *__restrict__ part, int d, int ffn,
+    const __half *__restrict__ p2, const float *__restrict__ p_bias, const float *__restrict__ t, int r,
+    int ffn_next, float thr_logit, uint64_t *__restrict__ mask_next, int first_word)
+{
+    extern __shared__ float ts[];
+    __shared__ float red[kDown2I4Waves][B][kDown2I4Cols];
+    __shared__ float logit_s[B][kLaOutNeurons];
+    const int bid = (int)blockIdx.x, n_fc2 = tiles * P;
+    if (bid < n_fc2) {  // uniform over the block
+        down2_i4_body<B>(red, bid % tiles, tiles, bid / tiles, P, q_down, s_down, b_down, h, idx, count_p, part,
+                         d, ffn);
+    } else {
+        pred_out_body<B, kLaOutNeurons>(ts, logit_s, bid - n_fc2, p2, p_bias, t, r, ffn_next, thr_logit, nullptr,
+                                        mask_next, first_word);
     }
 }
 

@@ -86,7 +86,8 @@ __device__ __forceinline__ void glue_commit(const GluePass<B, S> &gp, float *__r
 // issues together: 4 covers d <= 4096 in a single round trip, at 80 registers.
 // The body takes the block's number explicitly (bid) so that a launch can run it in a range of
 // its blocks beside another role; write_x: this block also writes x for the kernels that follow.
-template <int B, bool GLUE, int GS>
+// NT = threads of the launch (a block owns NT / 64 rows).
+template <int B, bool GLUE, int GS, int NT = kPredThreads>
 __device__ __forceinline__ void pred_hidden_body(float *xs, float (*ss_w)[B], const int bid, const bool write_x,
                                                  const __half *__restrict__ p1,
                                                  const float *__restrict__ x,
@@ -97,7 +98,7 @@ __device__ __forceinline__ void pred_hidden_body(float *xs, float (*ss_w)[B], co
     constexpr int U = 8;
     const int lane = threadIdx.x & 63, wave = wave_uniform(threadIdx.x >> 6);
     const int nch = (d + kChunk - 1) / kChunk, kpad = nch * kChunk;
-    const int m = bid * kPredWaves + wave;
+    const int m = bid * (NT / kWave) + wave;
     const bool live = m < r;
     const rsrc_t row = row_rsrc(p1, live ? m : 0, d, live);
 
@@ -110,20 +111,20 @@ __device__ __forceinline__ void pred_hidden_body(float *xs, float (*ss_w)[B], co
 #pragma unroll
         for (int b = 0; b < B; ++b) ss[b] = 0.f;
         constexpr int S = GS;  // strides whose loads are issued together
-        constexpr int step = kPredThreads * 4;
+        constexpr int step = NT * 4;
         bool issued = false;
         const rsrc_t xr = make_rsrc(x, (uint32_t)B * (uint32_t)d * 4u);
         const uint32_t pbytes = (uint32_t)ypstride * 4u;  // distance between partials
         const rsrc_t yr = make_rsrc(yp, (uint32_t)(ny - 1) * pbytes + (uint32_t)B * (uint32_t)d * 4u);
         for (int e0 = threadIdx.x * 4; e0 < kpad; e0 += step * S) {
             GluePass<B, S> gp;
-            glue_issue<B, S, kPredThreads>(gp, xr, yr, pbytes, ny, d, e0);
+            glue_issue<B, S, NT>(gp, xr, yr, pbytes, ny, d, e0);
             // the row's own loads queue up behind the first pass of activations
             if (!issued) {
                 load_group<U>(g, row, 0, lane);
                 issued = true;
             }
-            glue_commit<B, S, kPredThreads>(gp, xs, kpad, b0, e0, ss);
+            glue_commit<B, S, NT>(gp, xs, kpad, b0, e0, ss);
         }
         if (!issued) load_group<U>(g, row, 0, lane);  // threads past a short vector
 #pragma unroll
@@ -136,11 +137,11 @@ __device__ __forceinline__ void pred_hidden_body(float *xs, float (*ss_w)[B], co
         for (int b = 0; b < B; ++b) {
             float tot = 0.f;
 #pragma unroll
-            for (int k = 0; k < kPredWaves; ++k) tot += ss_w[k][b];
+            for (int k = 0; k < NT / kWave; ++k) tot += ss_w[k][b];
             scale[b] = tot > 0.f ? sqrtf((float)d / tot) : 0.f;
         }
         if (write_x) {
-            for (int e = threadIdx.x * 4; e < d; e += kPredThreads * 4) {
+            for (int e = threadIdx.x * 4; e < d; e += NT * 4) {
 #pragma unroll
                 for (int b = 0; b < B; ++b) {
                     const float4 v = *reinterpret_cast<const float4 *>(xs + b * kpad + lds_slot(e));

@@ -198,6 +198,9 @@ hipError_t allow_lds_for_batch()
         if (e == hipSuccess) e = allow_lds(pf::k_la_up_hidden<B, 1, false>);
         if (e == hipSuccess) e = allow_lds(pf::k_la_up_hidden<B, 1, true>);
         if (e == hipSuccess) e = allow_lds(pf::k_la_down_out<B>);
+        if (e == hipSuccess) e = allow_lds(pf::k_la_up_hidden_i4<B, 0>);
+        if (e == hipSuccess) e = allow_lds(pf::k_la_up_hidden_i4<B, 1>);
+        if (e == hipSuccess) e = allow_lds(pf::k_la_down_out_i4<B>);
     }
     return e;
 }
@@ -933,6 +936,94 @@ pf_status stack_enqueue_lookahead_merged_mfma(pf_ctx *ctx, pf_layer *const *laye
     return launch_glue(ctx, cur, ctx->ypart, ny, d, B, x_out, st);
 }
 
+// Whether a stack can run look-ahead prediction in the two-launch form of the int4 kernels:
+// int4 layers at a batch of at most 3 whose staged input fits LDS in one piece.
+bool la_merged_i4_ok(const pf_ctx *ctx, pf_layer *const *layers, int n_layers, int B)
+{
+    if (B > 3) return false;
+    for (int l = 0; l < n_layers; ++l) {
+        const pf_layer_desc &D = layers[l]->desc;
+        if (D.wtype != PF_W_INT4_G128) return false;
+        const size_t lds = ((size_t)B * kpad_i4(D.d) + pf::kStageScrap) * sizeof(float) + pf::up_mask_lds_bytes(D.ffn);
+        if (lds > (size_t)ctx->lds_budget) return false;
+    }
+    return true;
+}
+
+// One decode step with look-ahead prediction over int4 layers: glue, then [FC1 of layer l |
+// hidden layer of predictor l+1], then [FC2 of layer l | output layer of predictor l+1].
+pf_status stack_enqueue_lookahead_merged_i4(pf_ctx *ctx, pf_layer *const *layers, int n_layers,
+                                            const float *x, int B, float *x_out, hipStream_t st)
+{
+    uint64_t *masks[2] = {ctx->mask_words, ctx->mask_words2};
+    const int d = layers[0]->desc.d;
+    pf_status s = launch_predict(ctx, layers[0], x, nullptr, 0, nullptr, B, nullptr, masks[0], st);
+    if (s != PF_OK) return s;
+    int ny = 1;
+    const float *cur = x;
+    for (int l = 0; l < n_layers; ++l) {
+        const pf_layer *L = layers[l];
+        const pf_layer *N = l + 1 < n_layers ? layers[l + 1] : nullptr;
+        const pf_layer_desc &D = L->desc;
+        if (l > 0) {  // the int4 FC1 reads the layer input from memory
+            float *xn = ctx->xbuf[l & 1];
+            s = launch_glue(ctx, cur, ctx->ypart, ny, d, B, xn, st);
+            if (s != PF_OK) return s;
+            cur = xn;
+        }
+        const bool gated = D.act != PF_ACT_RELU;
+        const int n_hid = N ? cdiv(N->desc.r, pf::kUpI4Waves) : 0;
+        int n_up = cdiv(D.ffn, pf::kUpI4Waves);
+        if (n_up > ctx->up_grid_cap_i4) n_up = ctx->up_grid_cap_i4;
+        size_t lds1 = ((size_t)B * kpad_i4(D.d) + pf::kStageScrap) * sizeof(float) + pf::up_mask_lds_bytes(D.ffn);
+        const size_t lds_hid = ((size_t)B * kpad_of(D.d) + pf::kStageScrap) * sizeof(float);
+        if (lds1 < lds_hid) lds1 = lds_hid;
+        {
+            ProfScope ps(ctx, K_LA_UP_HIDDEN);
+#define PF_LA1I(ACT)                                                                                  \
+    PF_SWITCH_B3(B, PF_LAUNCH(ps, (pf::k_la_up_hidden_i4<BT, ACT>), dim3(n_up + n_hid),               \
+                              dim3(pf::kUpI4Threads), lds1, st, n_hid,                                \
+                              static_cast<const __half *>(N ? N->w.p1 : nullptr), ctx->t,             \
+                              N ? N->desc.r : 0, static_cast<const uint8_t *>(L->w.w_up),             \
+                              static_cast<const __half *>(L->w.s_up),                                 \
+                              static_cast<const uint8_t *>(L->w.w_gate),                              \
+                              static_cast<const __half *>(L->w.s_gate), L->w.b_up, cur,               \
+                              (const uint64_t *)masks[l & 1], ctx->idx, ctx->count, ctx->h,           \
+                              pf::h_stride(B), D.d, D.ffn, up_floor_of(D)))
+            if (gated) { PF_LA1I(1); }
+            else { PF_LA1I(0); }
+#undef PF_LA1I
+        }
+        ctx->last_mask = masks[l & 1];
+        ctx->last_idx = ctx->idx;
+        ctx->last_count = ctx->count;
+        const int tiles = cdiv(D.d, pf::kDown2I4Cols);
+        int P = ctx->down_split > 0 ? ctx->down_split : ctx->num_cu / tiles;
+        if (P < 1) P = 1;
+        if (P > pf::kDown2MaxSplit) P = pf::kDown2MaxSplit;
+        const int n_out = N ? (N->desc.ffn - N->always_on) / pf::kLaOutNeurons : 0;
+        const size_t lds2 = N ? ((size_t)B * kpad_of(N->desc.r) + pf::kStageScrap) * sizeof(float) : 0;
+        {
+            ProfScope ps(ctx, K_LA_DOWN_OUT);
+            PF_SWITCH_B3(B, PF_LAUNCH(ps, (pf::k_la_down_out_i4<BT>), dim3(tiles * P + n_out),
+                                      dim3(pf::kDown2I4Threads), lds2, st, tiles, P,
+                                      static_cast<const uint8_t *>(L->w.w_down),
+                                      static_cast<const __half *>(L->w.s_down), L->w.b_down,
+                                      (const float *)ctx->h, (const int32_t *)ctx->idx,
+                                      (const int32_t *)ctx->count, ctx->ypart, D.d, D.ffn,
+                                      static_cast<const __half *>(N ? N->w.p2 : nullptr),
+                                      N ? N->w.p_bias : nullptr, (const float *)ctx->t,
+                                      N ? N->desc.r : 0, N ? N->desc.ffn : 0, N ? N->thr_logit : 0.f,
+                                      masks[(l + 1) & 1], N ? N->always_on / 64 : 0));
+        }
+        ny = P;
+        PF_HIP(ctx, hipGetLastError());
+        s = trace_mask(ctx, l, L, masks[l & 1], false, st);
+        if (s != PF_OK) return s;
+    }
+    return launch_glue(ctx, cur, ctx->ypart, ny, d, B, x_out, st);
+}
+
 pf_status stack_enqueue(pf_ctx *ctx, pf_layer *const *layers, int n_layers, const float *x, int B,
                         float *x_out, hipStream_t st)
 {
@@ -948,6 +1039,8 @@ pf_status stack_enqueue(pf_ctx *ctx, pf_layer *const *layers, int n_layers, cons
             return stack_enqueue_lookahead_merged(ctx, layers, n_layers, x, B, x_out, st);
         if ((form == 0 || form == 1) && la_merged_mfma_ok(ctx, layers, n_layers, B))
             return stack_enqueue_lookahead_merged_mfma(ctx, layers, n_layers, x, B, x_out, st);
+        if ((form == 0 || form == 1) && la_merged_i4_ok(ctx, layers, n_layers, B))
+            return stack_enqueue_lookahead_merged_i4(ctx, layers, n_layers, x, B, x_out, st);
         if (form == 0 || form == 1) form = layers[0]->desc.act == PF_ACT_RELU ? 2 : 3;
         return form == 2 ? stack_enqueue_lookahead(ctx, layers, n_layers, x, B, x_out, st)
                          : stack_enqueue_lookahead_serial(ctx, layers, n_layers, x, B, x_out, st);

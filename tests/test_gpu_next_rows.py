@@ -121,7 +121,15 @@ def test_stack_lookahead_on_matrix_cores_matches_oracle(pf, act, B):
     _lookahead_case(pf, act, B, d=512, r=128, two_launch=True)
 
 
-def _lookahead_case(pf, act, B, d, r, two_launch):
+@pytest.mark.parametrize("B", [1, 2, 3, 4])
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_REGLU, wl.ACT_DRELU])
+def test_stack_lookahead_over_int4_layers_matches_oracle(pf, act, B):
+    """The two-launch form built from the int4 kernels (batch <= 3; batch 4 takes the other
+    forms), rows of 640 elements = 5 quantisation groups, a ragged predictor rank."""
+    _lookahead_case(pf, act, B, d=640, r=136, two_launch=B <= 3, wtype=wl.W_INT4_G128)
+
+
+def _lookahead_case(pf, act, B, d, r, two_launch, wtype=wl.W_FP16):
     """Look-ahead prediction at distance 1 through pf_stack_step and a recorded plan against the
     oracle's look-ahead stack, in both forms the library has: two launches per layer whose block
     ranges run the next layer's predictor beside this layer's sparse kernels (fp16, batch <= 3),
@@ -134,7 +142,7 @@ def _lookahead_case(pf, act, B, d, r, two_launch):
     from oracle import pf_oracle
     from tests.util import oracle_lookahead_chain_on_device_sets
     n_layers = 4
-    cfg = small_cfg(d=d, ffn=1344, r=r, act=act, rate=0.1, layers=n_layers)
+    cfg = small_cfg(d=d, ffn=1344, r=r, act=act, wtype=wtype, rate=0.1, layers=n_layers)
     for seed in range(40, 60):
         lays = [wl.make_layer(cfg, l, seed, device="cuda") for l in range(n_layers)]
         Os = [oracle_layer(cfg, wl.to_host(t)) for t in lays]
