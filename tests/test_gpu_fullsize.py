@@ -141,10 +141,16 @@ def test_full_shape_stack_three_launch_form_matches_oracle(pf, oracle, name, B):
     check_output(out.cpu().numpy(), ref, name + " three-launch stack")
 
 
-@pytest.mark.parametrize("name,B", [("opt-6.7b", 1), ("opt-6.7b", 3), ("llama2-13b-reglu", 2), ("opt-30b", 2)])
+@pytest.mark.parametrize("name,B", [("opt-6.7b", 1), ("opt-6.7b", 3), ("llama2-13b-reglu", 2), ("opt-30b", 2),
+                                    # the same form from the matrix-core kernels ...
+                                    ("opt-30b", 4), ("opt-30b", 8), ("llama2-13b-reglu", 4),
+                                    ("bamboo-7b-drelu", 4),
+                                    # ... and from the int4 kernels
+                                    ("opt-175b-int4", 1)])
 def test_full_shape_lookahead_two_launch_form_matches_oracle(pf, oracle, name, B):
     """Three full-size layers with look-ahead prediction through the recorded plan, in the form
-    with two launches per layer (next layer's predictor beside this layer's sparse kernels):
+    with two launches per layer (next layer's predictor beside this layer's sparse kernels;
+    vector, matrix-core and int4 kernels):
     every layer's set against the oracle's look-ahead rule outside the score band, the output
     against the oracle's stack run on those sets."""
     cfg = wl.scaled(wl.CONFIGS[name], layers=3)
