@@ -383,6 +383,34 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
     return PF_OK;
 }
 
+// Row groups of FC2 (P): with `tiles` column tiles the launch has tiles * P workgroups, each
+// over 1/P of the listed rows.  One round of workgroups (<= one per CU) costs 1/P; two
+// workgroups share a CU at about 1.6 x the time of one while the batch is small enough for two
+// to be resident (measured at 112 and 128 tiles; at batch 8 the second workgroup waits); more
+// rounds cost a round each.  Ties go to the smaller P (fewer partial sums to add).
+inline int fc2_split(const pf_ctx *ctx, int tiles, int B)
+{
+    if (ctx->down_split > 0) return ctx->down_split < pf::kDown2MaxSplit ? ctx->down_split : pf::kDown2MaxSplit;
+    int best = 1;
+    double best_cost = 1e30;
+    for (int P = 1; P <= pf::kDown2MaxSplit; ++P) {
+        const int blocks = tiles * P;
+        double rounds;
+        if (blocks <= ctx->num_cu)
+            rounds = 1.0;
+        else if (B <= 4 && blocks <= 2 * ctx->num_cu)
+            rounds = 1.6;
+        else
+            rounds = (double)cdiv(blocks, ctx->num_cu);
+        const double cost = rounds / P;
+        if (cost < best_cost - 1e-9) {
+            best_cost = cost;
+            best = P;
+        }
+    }
+    return best;
+}
+
 inline int kpad_i4(int k) { return cdiv(k, pf::kI4Chunk) * pf::kI4Chunk; }
 
 // Sparse FFN over int4 weights (same launch structure as the fp16 one below).
@@ -427,9 +455,7 @@ pf_status launch_sparse_i4(pf_ctx *ctx, const pf_layer *L, const float *x, int B
     const int32_t *idx = from_mask ? ctx->idx : idx_in;
     const int32_t *count = from_mask ? ctx->count : count_in;
     const int tiles = cdiv(D.d, pf::kDown2I4Cols);
-    int P = ctx->down_split > 0 ? ctx->down_split : ctx->num_cu / tiles;
-    if (P < 1) P = 1;
-    if (P > pf::kDown2MaxSplit) P = pf::kDown2MaxSplit;
+    const int P = fc2_split(ctx, tiles, B);
     float *part = (ny_out || P > 1) ? ctx->ypart : y;
     {
         ProfScope ps(ctx, K_DOWN);
@@ -507,9 +533,7 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
     const int32_t *count = from_mask ? ctx->count : count_in;
     // row-split FC2: enough row groups per column tile to give every CU a workgroup
     const int tiles = cdiv(D.d, pf::kDown2Cols);
-    int P = ctx->down_split > 0 ? ctx->down_split : ctx->num_cu / tiles;
-    if (P < 1) P = 1;
-    if (P > pf::kDown2MaxSplit) P = pf::kDown2MaxSplit;
+    const int P = fc2_split(ctx, tiles, B);
     float *part = (ny_out || P > 1) ? ctx->ypart : y;
     {
         ProfScope ps(ctx, K_DOWN);
@@ -590,9 +614,7 @@ pf_status launch_layer_fused(pf_ctx *ctx, const pf_layer *L, const float *x, con
 #undef PF_OU
     }
     const int tiles = cdiv(D.d, pf::kDown2Cols);
-    int P = ctx->down_split > 0 ? ctx->down_split : ctx->num_cu / tiles;
-    if (P < 1) P = 1;
-    if (P > pf::kDown2MaxSplit) P = pf::kDown2MaxSplit;
+    const int P = fc2_split(ctx, tiles, B);
     {
         ProfScope ps(ctx, K_DOWN_MASK);
         const bool multi = cdiv(D.ffn / 64, 8 * P) > pf::down2m_batch(B);
@@ -904,6 +926,8 @@ pf_status stack_enqueue_lookahead_merged_mfma(pf_ctx *ctx, pf_layer *const *laye
         ctx->last_idx = ctx->idx;
         ctx->last_count = ctx->count;
         const int tiles = cdiv(D.d, pf::kDown2Cols);
+        // one round of FC2 workgroups here: the output-layer role fills the CUs beside them
+        // (measured: a second FC2 workgroup per CU costs this launch 4 %)
         int P = ctx->down_split > 0 ? ctx->down_split : ctx->num_cu / tiles;
         if (P < 1) P = 1;
         if (P > pf::kDown2MaxSplit) P = pf::kDown2MaxSplit;
@@ -998,9 +1022,7 @@ pf_status stack_enqueue_lookahead_merged_i4(pf_ctx *ctx, pf_layer *const *layers
         ctx->last_idx = ctx->idx;
         ctx->last_count = ctx->count;
         const int tiles = cdiv(D.d, pf::kDown2I4Cols);
-        int P = ctx->down_split > 0 ? ctx->down_split : ctx->num_cu / tiles;
-        if (P < 1) P = 1;
-        if (P > pf::kDown2MaxSplit) P = pf::kDown2MaxSplit;
+        const int P = fc2_split(ctx, tiles, B);
         const int n_out = N ? (N->desc.ffn - N->always_on) / pf::kLaOutNeurons : 0;
         const size_t lds2 = N ? ((size_t)B * kpad_of(N->desc.r) + pf::kStageScrap) * sizeof(float) : 0;
         {
