@@ -355,19 +355,26 @@ def test_neuron_table_and_always_on_prefix(pf, oracle, act, B):
     LP.set_neuron_table(None, 0)                  # back to a plain layer in stored numbering
 
 
-@pytest.mark.parametrize("form", ["list", "fused", "fused-strided", "lookahead"])
+@pytest.mark.parametrize("form", ["list", "fused", "fused-strided", "lookahead", "lookahead-matrix-cores",
+                                  "lookahead-int4"])
 def test_stack_of_hot_first_layers_with_always_on_prefix(pf, oracle, form):
     """Three hot-first layers with neuron tables and always-on prefixes through pf_stack_step in
     every form the stack has (list form, three-launch form with both segment layouts, two-launch
-    look-ahead): the mask trace (stored numbering) mapped through the tables against the
-    oracle's stack on the layers as the model numbers them."""
-    from tests.util import oracle_lookahead_chain_on_device_sets
-    cfg = small_cfg(d=520, ffn=1344, r=136, rate=0.12, layers=3)
-    B, A = 2, 192
+    look-ahead from the vector, matrix-core and int4 kernels): the mask trace (stored numbering)
+    mapped through the tables against the oracle's stack on the layers as the model numbers
+    them."""
+    if form == "lookahead-matrix-cores":
+        cfg, B = small_cfg(d=512, ffn=1344, r=128, rate=0.12, layers=3), 5
+    elif form == "lookahead-int4":
+        cfg, B = small_cfg(d=640, ffn=1344, r=136, rate=0.12, layers=3, wtype=wl.W_INT4_G128), 2
+    else:
+        cfg, B = small_cfg(d=520, ffn=1344, r=136, rate=0.12, layers=3), 2
+    A = 192
+    lookahead = form.startswith("lookahead")
     ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
     ctx.set_option(pf.OPT_FUSED, 0 if form == "list" else 2)
     ctx.set_option(pf.OPT_SEG_STRIDED, 1 if form == "fused-strided" else 0)
-    ctx.set_lookahead(1 if form == "lookahead" else 0)
+    ctx.set_lookahead(1 if lookahead else 0)
     lays = [wl.make_layer(cfg, l, seed=81, device="cuda") for l in range(cfg.layers)]
     Os = [oracle_layer(cfg, wl.to_host(t)) for t in lays]
     Ls, orders, keep = [], [], []
@@ -380,7 +387,7 @@ def test_stack_of_hot_first_layers_with_always_on_prefix(pf, oracle, form):
         Ls.append(L)
         orders.append(order)
         keep.append((perm, table))
-    ctx.set_lookahead(1 if form == "lookahead" else 0)
+    ctx.set_lookahead(1 if lookahead else 0)
     x0 = wl.make_inputs(cfg, 0, seed=82, batch=B, device="cuda")
     trace = MaskTrace(ctx, cfg.layers, cfg.ffn)
     out = torch.full_like(x0, float("nan"))
@@ -391,7 +398,7 @@ def test_stack_of_hot_first_layers_with_always_on_prefix(pf, oracle, form):
     ctx.set_mask_trace(None)
     if form.startswith("fused"):
         assert stats["k_out_up"][0] == cfg.layers - 1
-    if form == "lookahead":
+    if lookahead:
         assert stats["k_la_down_out"][0] == cfg.layers
     masks, forced = [], []
     for l, m in enumerate(trace.masks()):
@@ -402,7 +409,7 @@ def test_stack_of_hot_first_layers_with_always_on_prefix(pf, oracle, form):
         f = np.zeros(cfg.ffn, bool)
         f[orders[l][:A]] = True
         forced.append(f)
-    if form == "lookahead":
+    if lookahead:
         xo, inputs = x0.cpu().numpy(), []
         for l, (O, m) in enumerate(zip(Os, masks)):
             inputs.append(xo)
