@@ -161,6 +161,21 @@ __device__ __forceinline__ float4 ld16_f32(rsrc_t r, uint32_t byte_off)
                        __uint_as_float(v.w));
 }
 
+// 16-byte cacheable load, raw bits.
+__device__ __forceinline__ uint4 ld16_cached(rsrc_t r, uint32_t byte_off)
+{
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// fp32 -> fp16 hi (rounded) + fp16 lo (residual): v = hi + lo to 2^-21 |v|.  The matrix-core
+// kernels multiply fp16 weights by both halves, so activations stay fp32-exact.
+__device__ __forceinline__ void split_f32(float v, _Float16 &hi, _Float16 &lo)
+{
+    hi = (_Float16)v;
+    lo = (_Float16)(v - (float)hi);
+}
+
 __device__ __forceinline__ int wave_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 // Descriptor of row `i` (wave-uniform) of a neuron-major fp16 matrix with rows of K values;

@@ -81,8 +81,9 @@ __global__ __launch_bounds__(kDown2Threads) void k_la_down_out(
 
 // ---------------------------------------------------------------------------------------
 // The same two launches for batches on the matrix cores (batch >= 4, or 3 with long rows),
-// from the matrix-core kernels' bodies.  These read the layer input from memory, so a glue
-// kernel of its own runs in front of the first launch.  Ungated layers: two workgroups of
+// from the matrix-core kernels' bodies.  These read the layer input from memory, as split
+// fp16 planes, so a glue kernel of its own (or k_split for the first layer) runs in front of
+// the first launch.  Ungated layers: two workgroups of
 // either role fit a CU.  The gated FC1 needs 128 KB of LDS per workgroup, so there a CU holds
 // one workgroup at a time and the hidden-layer role follows FC1 rather than sharing the CUs.
 static_assert(kMfmaThreads == kDown2Threads, "all roles of these launches use 512 threads");
@@ -94,7 +95,7 @@ template <int ACT>
 __global__ __launch_bounds__(kMfmaThreads) void k_la_up_hidden_mfma(
     int n_hid, const __half *__restrict__ p1, float *__restrict__ t, int r,
     const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
-    const float *__restrict__ b_up, const float *__restrict__ x, int B,
+    const float *__restrict__ b_up, const void *__restrict__ xs, int B,
     const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
     int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor)
 {
@@ -105,10 +106,11 @@ __global__ __launch_bounds__(kMfmaThreads) void k_la_up_hidden_mfma(
     __shared__ float logit_s[16][16];
     const int n_up = (int)gridDim.x - n_hid, bid = (int)blockIdx.x;
     if (bid < n_up) {  // uniform over the block
-        up_mfma_body<ACT, true>(dyn_lds64, wave_tot, irow, brow, bid, n_up, w_up, w_gate, b_up, x, B,
-                                nullptr, nullptr, mask_words, idx_out, count_out, h, hs, d, ffn, up_floor);
+        up_mfma_body<ACT, true, true>(dyn_lds64, wave_tot, irow, brow, bid, n_up, w_up, w_gate, b_up, xs, B,
+                                      nullptr, nullptr, mask_words, idx_out, count_out, h, hs, d, ffn, up_floor);
     } else {
-        rows_mfma_body<8, 512, 0>(dyn_lds64, logit_s, bid - n_up, p1, x, B, d, r, nullptr, 0.f, t, nullptr, 0);
+        rows_mfma_body<8, 512, 0, true>(dyn_lds64, logit_s, bid - n_up, p1, xs, B, d, r, nullptr, 0.f, t, nullptr,
+                                        0);
     }
 }
 
@@ -133,8 +135,8 @@ __global__ __launch_bounds__(kMfmaThreads) void k_la_down_out_mfma(
         down2_body<B>(reinterpret_cast<float(*)[B][kDown2Cols]>(dyn_lds64), bid % tiles, bid / tiles, P, w_down,
                       b_down, h, idx, count_p, part, d, ffn);
     } else {
-        rows_mfma_body<64, 64, 1>(dyn_lds64, logit_s, bid - n_fc2, p2, t, B, r, ffn_next, p_bias, thr_logit,
-                                  nullptr, mask_next, first_word);
+        rows_mfma_body<64, 64, 1, false>(dyn_lds64, logit_s, bid - n_fc2, p2, t, B, r, ffn_next, p_bias, thr_logit,
+                                         nullptr, mask_next, first_word);
     }
 }
 

@@ -48,15 +48,51 @@ union Half8Bits {
     half8_t h;
 };
 
-// Split 8 fp32 values into fp16 hi (rounded) and fp16 lo (residual) vectors.
-__device__ __forceinline__ void split_hi_lo(const float4 &a, const float4 &b, half8_t &hi, half8_t &lo)
+// The B operand (activations) of one K step for a lane: 8 consecutive elements of its token,
+// as loaded.  From fp32 activations: elements 0-3 and 4-7, split into fp16 hi (rounded) + lo
+// (residual) when used.  From split planes (XS; written by the glue kernels or k_split): the 8
+// hi halfs and the 8 lo halfs, used as they are -- the split then costs the matrix-core
+// kernels nothing (it was 40 vector operations per K step in every workgroup).
+struct XRaw {
+    uint4 a, b;
+};
+
+// elem = index of the lane's first element in [B][K] (ok: the lane has a token and k < K);
+// plane_bytes = distance between the hi and lo planes.
+template <bool XS>
+__device__ __forceinline__ XRaw load_xraw(rsrc_t xr, uint32_t elem, bool ok, uint32_t plane_bytes)
 {
-    const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    XRaw r;
+    if (XS) {
+        r.a = ld16_cached(xr, ok ? elem * 2u : kOobOffset);
+        r.b = ld16_cached(xr, ok ? elem * 2u + plane_bytes : kOobOffset);
+    } else {
+        r.a = ld16_cached(xr, ok ? elem * 4u : kOobOffset);
+        r.b = ld16_cached(xr, ok ? elem * 4u + 16u : kOobOffset);
+    }
+    return r;
+}
+
+template <bool XS>
+__device__ __forceinline__ void finish_x(const XRaw &r, half8_t &hi, half8_t &lo)
+{
+    if (XS) {
+        Half8Bits h, l;
+        h.u = r.a;
+        l.u = r.b;
+        hi = h.h;
+        lo = l.h;
+    } else {
+        const float v[8] = {__uint_as_float(r.a.x), __uint_as_float(r.a.y), __uint_as_float(r.a.z),
+                            __uint_as_float(r.a.w), __uint_as_float(r.b.x), __uint_as_float(r.b.y),
+                            __uint_as_float(r.b.z), __uint_as_float(r.b.w)};
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const _Float16 h = (_Float16)v[e];
-        hi[e] = h;
-        lo[e] = (_Float16)(v[e] - (float)h);
+        for (int e = 0; e < 8; ++e) {
+            _Float16 h, l;
+            split_f32(v[e], h, l);
+            hi[e] = h;
+            lo[e] = l;
+        }
     }
 }
 
@@ -98,7 +134,7 @@ struct UpMfmaArgs {
 };
 
 // The list slots [j_begin, j_end) of a block in passes of R rows (R / 16 MFMA tiles).
-template <int R, int ACT, bool FROM_MASK>
+template <int R, int ACT, bool FROM_MASK, bool XS>
 __device__ __forceinline__ void up_mfma_passes(const UpMfmaArgs &a)
 {
     constexpr bool GATED = (ACT == 1);
@@ -111,7 +147,9 @@ __device__ __forceinline__ void up_mfma_passes(const UpMfmaArgs &a)
     const int row16 = lane & 15, kg = lane >> 4;
     char *slot = a.slots + (size_t)wave * NM * kMfmaSlotBytes;  // this wave's: up, then gate
     const int d = a.d, n = a.n;
-    const uint32_t xoff = row16 < a.B ? ((uint32_t)row16 * (uint32_t)d + (uint32_t)kg * 8u) * 4u : kOobOffset;
+    const bool xlane = row16 < a.B;  // this lane supplies a token's B operands
+    const uint32_t xelem = (uint32_t)row16 * (uint32_t)d + (uint32_t)kg * 8u;
+    const uint32_t xplane = (uint32_t)a.B * (uint32_t)d * 2u;
     const int nchunks = (d + KC - 1) / KC;
 
     for (int j0 = a.j_begin; j0 < a.j_end; j0 += R) {
@@ -169,13 +207,11 @@ __device__ __forceinline__ void up_mfma_passes(const UpMfmaArgs &a)
             if (GATED) mfma_issue_chunk<R>(a.wg, slot + kMfmaSlotBytes, rowoff, c, d, lane);
         }
         while (c < nchunks) {  // wave-uniform
-            float4 xa[STEPS], xb[STEPS];
+            XRaw xv[STEPS];
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
                 const int k = c * KC + s * 32;
-                const uint32_t o = (k < d && xoff != kOobOffset) ? xoff + (uint32_t)k * 4u : kOobOffset;
-                xa[s] = ld16_f32(a.xr, o);
-                xb[s] = ld16_f32(a.xr, o != kOobOffset ? o + 16u : kOobOffset);
+                xv[s] = load_xraw<XS>(a.xr, xelem + (uint32_t)k, xlane && k < d, xplane);
             }
             Half8Bits au[T][STEPS], ag[T][STEPS];
 #pragma unroll
@@ -198,7 +234,7 @@ __device__ __forceinline__ void up_mfma_passes(const UpMfmaArgs &a)
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
                 half8_t hi, lo;
-                split_hi_lo(xa[s], xb[s], hi, lo);
+                finish_x<XS>(xv[s], hi, lo);
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
                     if (t >= ntile) break;
@@ -262,11 +298,12 @@ __device__ __forceinline__ void up_mfma_passes(const UpMfmaArgs &a)
 // wrote, and the wait between the two is the compiler's, which places it only while it takes
 // the two accesses to alias.  Inlining a function with restrict parameters tags its accesses
 // with no-alias scopes, and with those the waits were dropped (wrong sums on the device).
-template <int ACT, bool FROM_MASK>
+// XS: x points at the split planes of the activations (see XRaw) instead of fp32 values.
+template <int ACT, bool FROM_MASK, bool XS>
 __device__ __forceinline__ void up_mfma_body(
     uint64_t *dyn_lds64, uint32_t *wave_tot, int *irow, float *brow, const int bid, const int nblocks,
     const __half *w_up, const __half *w_gate,
-    const float *b_up, const float *x, int B,
+    const float *b_up, const void *x, int B,
     const int32_t *idx_in, const int32_t *count_in,
     const uint64_t *mask_words, int32_t *idx_out,
     int32_t *count_out, float *h, int hs, int d, int ffn, float up_floor)
@@ -314,16 +351,16 @@ __device__ __forceinline__ void up_mfma_body(
     a.j_end = min(n, a.j_begin + rpb);
     PF_TSTAMP(2, 1);
     if (rpb <= 16)
-        up_mfma_passes<16, ACT, FROM_MASK>(a);
+        up_mfma_passes<16, ACT, FROM_MASK, XS>(a);
     else
-        up_mfma_passes<32, ACT, FROM_MASK>(a);
+        up_mfma_passes<32, ACT, FROM_MASK, XS>(a);
     PF_TSTAMP(2, 5);
 }
 
-template <int ACT, bool FROM_MASK>
+template <int ACT, bool FROM_MASK, bool XS>
 __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     const __half *__restrict__ w_up, const __half *__restrict__ w_gate,
-    const float *__restrict__ b_up, const float *__restrict__ x, int B,
+    const float *__restrict__ b_up, const void *__restrict__ x, int B,
     const int32_t *__restrict__ idx_in, const int32_t *__restrict__ count_in,
     const uint64_t *__restrict__ mask_words, int32_t *__restrict__ idx_out,
     int32_t *__restrict__ count_out, float *__restrict__ h, int hs, int d, int ffn, float up_floor)
@@ -332,7 +369,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_up_mfma(
     __shared__ uint32_t wave_tot[kMfmaWaves];
     __shared__ int irow[32];
     __shared__ float brow[32];
-    up_mfma_body<ACT, FROM_MASK>(dyn_lds64, wave_tot, irow, brow, (int)blockIdx.x, (int)gridDim.x, w_up, w_gate,
+    up_mfma_body<ACT, FROM_MASK, XS>(dyn_lds64, wave_tot, irow, brow, (int)blockIdx.x, (int)gridDim.x, w_up, w_gate,
                                  b_up, x, B, idx_in, count_in, mask_words, idx_out, count_out, h, hs, d,
                                  ffn, up_floor);
 }
@@ -372,10 +409,11 @@ __device__ __forceinline__ void rows_mfma_issue(rsrc_t w, char *slot, uint32_t r
 
 // Body: bid0 = the block's number within its role, logit_s = [16][16 * tiles] floats of LDS.
 // No restrict qualifiers, for the same reason as in up_mfma_body.
-template <int R, int KC, int EPI>
+// XS: v points at the split planes of the activations (see XRaw) instead of fp32 values.
+template <int R, int KC, int EPI, bool XS>
 __device__ __forceinline__ void rows_mfma_body(
     uint64_t *dyn_lds64, float (*logit_s)[16 * ((R + 15) / 16)], const int bid0,
-    const __half *w, const float *v, int B, int K, int nrows,
+    const __half *w, const void *v, int B, int K, int nrows,
     const float *p_bias, float thr_logit, float *out,
     uint64_t *mask_words, int first_word)
 {
@@ -401,7 +439,9 @@ __device__ __forceinline__ void rows_mfma_body(
     const rsrc_t wr = make_rsrc(w, (uint32_t)nrows * (uint32_t)K * 2u);
     const rsrc_t vr = make_rsrc(v, (uint32_t)B * (uint32_t)K * 4u);
     const uint32_t row_bytes = (uint32_t)K * 2u, row0_off = (uint32_t)r0 * row_bytes;
-    const uint32_t voff = row16 < B ? ((uint32_t)row16 * (uint32_t)K + (uint32_t)kg * 8u) * 4u : kOobOffset;
+    const bool vlane = row16 < B;  // this lane supplies a token's B operands
+    const uint32_t velem = (uint32_t)row16 * (uint32_t)K + (uint32_t)kg * 8u;
+    const uint32_t vplane = (uint32_t)B * (uint32_t)K * 2u;
     const int nchunks = (K + KC - 1) / KC;
 
     PF_TSTAMP(EPI, 0);
@@ -412,20 +452,18 @@ __device__ __forceinline__ void rows_mfma_body(
     // are fetched one sub-block ahead of their use, so that their L2 round trip overlaps the
     // matrix work of the sub-block before
     constexpr int NSB = STEPS / SB;
-    float4 xa[2][SB], xb[2][SB];
-    auto load_x = [&](int ch, int j, float4 (&pa)[SB], float4 (&pb)[SB]) {
+    XRaw xv[2][SB];
+    auto load_x = [&](int ch, int j, XRaw (&px)[SB]) {
 #pragma unroll
         for (int s = 0; s < SB; ++s) {
             const int k = ch * KC + (j * SB + s) * 32;
-            const uint32_t o = (k < K && voff != kOobOffset) ? voff + (uint32_t)k * 4u : kOobOffset;
-            pa[s] = ld16_f32(vr, o);
-            pb[s] = ld16_f32(vr, o != kOobOffset ? o + 16u : kOobOffset);
+            px[s] = load_xraw<XS>(vr, velem + (uint32_t)k, vlane && k < K, vplane);
         }
     };
     int c = wave;
     if (c < nchunks) {
         rows_mfma_issue<R, KC>(wr, slot, row0_off, row_bytes, nleft, c, K, lane);
-        load_x(c, 0, xa[0], xb[0]);
+        load_x(c, 0, xv[0]);
     }
     // output layer: the biases of the rows this thread finishes, fetched behind the first chunk
     // (read only after the chunk loop: their latency is off the block's tail)
@@ -454,16 +492,16 @@ __device__ __forceinline__ void rows_mfma_body(
                             slot + row * (KC * 2) + ((4 * (j * SB + s) + kg) ^ (row & 7)) * 16);
                 }
             if (j + 1 < NSB) {
-                load_x(c, j + 1, xa[nxt], xb[nxt]);
+                load_x(c, j + 1, xv[nxt]);
             } else if (cn < nchunks) {  // last sub-block: refill the slot, fetch the next chunk's x
                 __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the slot is all in registers
                 rows_mfma_issue<R, KC>(wr, slot, row0_off, row_bytes, nleft, cn, K, lane);
-                load_x(cn, 0, xa[nxt], xb[nxt]);
+                load_x(cn, 0, xv[nxt]);
             }
 #pragma unroll
             for (int s = 0; s < SB; ++s) {
                 half8_t hi, lo;
-                split_hi_lo(xa[cur][s], xb[cur][s], hi, lo);
+                finish_x<XS>(xv[cur][s], hi, lo);
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[t][s].h, hi, acc[t], 0, 0, 0);
@@ -473,10 +511,7 @@ __device__ __forceinline__ void rows_mfma_body(
         }
         if (NSB & 1) {  // the next chunk starts from buffer 0 again
 #pragma unroll
-            for (int s = 0; s < SB; ++s) {
-                xa[0][s] = xa[1][s];
-                xb[0][s] = xb[1][s];
-            }
+            for (int s = 0; s < SB; ++s) xv[0][s] = xv[1][s];
         }
         c = cn;
     }
@@ -517,9 +552,9 @@ __device__ __forceinline__ void rows_mfma_body(
     PF_TSTAMP(EPI, 2);
 }
 
-template <int R, int KC, int EPI>
+template <int R, int KC, int EPI, bool XS>
 __global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
-    const __half *__restrict__ w, const float *__restrict__ v, int B, int K, int nrows,
+    const __half *__restrict__ w, const void *__restrict__ v, int B, int K, int nrows,
     const float *__restrict__ p_bias, float thr_logit, float *__restrict__ out,
     uint64_t *__restrict__ mask_words, int first_word, const int32_t *__restrict__ skip)
 {
@@ -535,7 +570,7 @@ __global__ __launch_bounds__(kMfmaThreads) void k_rows_mfma(
         }
         return;
     }
-    rows_mfma_body<R, KC, EPI>(dyn_lds64, logit_s, (int)blockIdx.x, w, v, B, K, nrows, p_bias, thr_logit,
+    rows_mfma_body<R, KC, EPI, XS>(dyn_lds64, logit_s, (int)blockIdx.x, w, v, B, K, nrows, p_bias, thr_logit,
                                out, mask_words, first_word);
 }
 

@@ -354,6 +354,21 @@ __global__ __launch_bounds__(256) void k_combine(const float *__restrict__ part,
 // Stack glue: x_next[b] = sign(b, .) * (x[b] + y[b]) * sqrt(d) / ||x[b] + y[b]||_2.  grid = B.
 constexpr int kGlueThreads = 1024;
 
+// Four consecutive values as fp16 hi + lo at element `at` of the hi plane and of the lo plane
+// `plane` halfs behind it.
+__device__ __forceinline__ void store_split4(__half *xs, size_t plane, size_t at, const float4 &o)
+{
+    _Float16 hi[4], lo[4];
+    split_f32(o.x, hi[0], lo[0]);
+    split_f32(o.y, hi[1], lo[1]);
+    split_f32(o.z, hi[2], lo[2]);
+    split_f32(o.w, hi[3], lo[3]);
+    typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+    *reinterpret_cast<half4_t *>(reinterpret_cast<_Float16 *>(xs) + at) = (half4_t){hi[0], hi[1], hi[2], hi[3]};
+    *reinterpret_cast<half4_t *>(reinterpret_cast<_Float16 *>(xs) + plane + at) =
+        (half4_t){lo[0], lo[1], lo[2], lo[3]};
+}
+
 // x_next may alias x: every element is read and written by the same thread.
 // y may come as ny partial sums [ny][B][d] (see k_down2): they are added in order.
 // d <= kGlueMaxD: a thread keeps its (up to 4) float4 sums in registers, so every load of the
@@ -361,8 +376,10 @@ constexpr int kGlueThreads = 1024;
 // reduction, then the stores.
 constexpr int kGlueMaxD = kGlueThreads * 4 * 4;
 
+// xs_next (may be null): the same values split into fp16 hi and lo planes, [B][d] each, lo
+// plane B * d halfs behind the hi plane (the operand format of the matrix-core kernels).
 __global__ __launch_bounds__(kGlueThreads) void k_glue(const float *x, const float *__restrict__ y,
-                                                       int ny, float *x_next, int d)
+                                                       int ny, float *x_next, int d, __half *xs_next)
 {
     __shared__ float wsum[kGlueThreads / kWave];
     const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -400,15 +417,17 @@ __global__ __launch_bounds__(kGlueThreads) void k_glue(const float *x, const flo
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int e = (i * kGlueThreads + (int)threadIdx.x) * 4;
-        if (e < d)
-            *reinterpret_cast<float4 *>(x_next + (size_t)b * d + e) =
-                make_float4(v[i].x * scale, v[i].y * scale, v[i].z * scale, v[i].w * scale);
+        if (e < d) {
+            const float4 o = make_float4(v[i].x * scale, v[i].y * scale, v[i].z * scale, v[i].w * scale);
+            *reinterpret_cast<float4 *>(x_next + (size_t)b * d + e) = o;
+            if (xs_next != nullptr) store_split4(xs_next, (size_t)gridDim.x * d, (size_t)b * d + e, o);
+        }
     }
 }
 
 // The same for any d (two passes over the inputs).
 __global__ __launch_bounds__(kGlueThreads) void k_glue_long(const float *x, const float *__restrict__ y,
-                                                            int ny, float *x_next, int d)
+                                                            int ny, float *x_next, int d, __half *xs_next)
 {
     __shared__ float wsum[kGlueThreads / kWave];
     const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -433,8 +452,23 @@ __global__ __launch_bounds__(kGlueThreads) void k_glue_long(const float *x, cons
     const float scale = tot > 0.f ? sqrtf((float)d / tot) : 0.f;
     for (int c = threadIdx.x; c < d; c += kGlueThreads) {
         const float v = (xb[c] + ysum(c)) * scale;
-        x_next[(size_t)b * d + c] = __uint_as_float(__float_as_uint(v) ^ glue_sign_bit((uint32_t)b, (uint32_t)c));
+        const float o = __uint_as_float(__float_as_uint(v) ^ glue_sign_bit((uint32_t)b, (uint32_t)c));
+        x_next[(size_t)b * d + c] = o;
+        if (xs_next != nullptr) {
+            _Float16 hi, lo;
+            split_f32(o, hi, lo);
+            reinterpret_cast<_Float16 *>(xs_next)[(size_t)b * d + c] = hi;
+            reinterpret_cast<_Float16 *>(xs_next)[(size_t)gridDim.x * d + (size_t)b * d + c] = lo;
+        }
     }
+}
+
+// The split planes of a caller's activations x[n] (n = B * d, a multiple of 4): xs[0 .. n) hi,
+// xs[n .. 2n) lo.  grid = ceil(n / 1024), block = 256.
+__global__ __launch_bounds__(256) void k_split(const float *__restrict__ x, __half *__restrict__ xs, int n)
+{
+    const int e = ((int)blockIdx.x * 256 + (int)threadIdx.x) * 4;
+    if (e < n) store_split4(xs, (size_t)n, (size_t)e, *reinterpret_cast<const float4 *>(x + e));
 }
 
 }  // namespace pf

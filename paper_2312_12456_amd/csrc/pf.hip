@@ -76,6 +76,13 @@ struct pf_ctx {
     float *h = nullptr;              // [max_ffn][h_stride(batch)] FC1 outputs, by list slot
     float *ypart = nullptr;          // [4][max_batch][max_d] FC2 output as partial sums
     float *xbuf[2] = {nullptr, nullptr};  // [max_batch][max_d] layer inputs inside pf_stack_step
+    // fp16 hi + lo planes of the activations the matrix-core kernels read ([2][B][d] halfs each;
+    // two buffers, used in turn); split_src = the fp32 array whose split xsplit[split_cur] holds,
+    // valid within one entry-point call only (reset by check_batch)
+    __half *xsplit[2] = {nullptr, nullptr};
+    const float *split_src = nullptr;
+    int split_cur = 0;
+    bool split_off = false;  // set while kernels are enqueued on a second stream
     hipStream_t capture_stream = nullptr;
     // look-ahead mode: predictors on a stream of their own, masks double-buffered
     int lookahead = 0;
@@ -207,12 +214,17 @@ hipError_t allow_lds_for_batch()
 
 hipError_t allow_lds_mfma()
 {
-    hipError_t e = allow_lds(pf::k_up_mfma<0, false>);
-    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<0, true>);
-    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, false>);
-    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, true>);
-    if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<8, 512, 0>);
-    if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<64, 64, 1>);
+    hipError_t e = allow_lds(pf::k_up_mfma<0, false, false>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<0, true, false>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, false, false>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, true, false>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<0, false, true>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<0, true, true>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, false, true>);
+    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, true, true>);
+    if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<8, 512, 0, true>);
+    if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<8, 512, 0, false>);
+    if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<64, 64, 1, false>);
     if (e == hipSuccess) e = allow_lds(pf::k_la_up_hidden_mfma<0>);
     if (e == hipSuccess) e = allow_lds(pf::k_la_up_hidden_mfma<1>);
     if (e == hipSuccess) e = allow_lds(pf::k_la_down_out_mfma<3>);
@@ -240,6 +252,7 @@ hipError_t allow_lds_all()
 
 pf_status check_batch(pf_ctx *ctx, const pf_layer *layer, const void *x, int B)
 {
+    if (ctx) ctx->split_src = nullptr;  // no split planes carry over from an earlier call
     if (!ctx) return PF_EINVAL;
     if (!layer || !x) return fail(ctx, PF_EINVAL, "null layer or input");
     if (layer->ctx != ctx) return fail(ctx, PF_EINVAL, "layer belongs to another context");
@@ -279,7 +292,9 @@ struct ProfScope {
 
 // ---- launches ------------------------------------------------------------------------
 pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int ny, int d, int B,
-                      float *x_next, hipStream_t st);
+                      float *x_next, hipStream_t st, bool split = false);
+const __half *split_of(const pf_ctx *ctx, const float *x);
+pf_status ensure_split(pf_ctx *ctx, const float *x, int B, int d, hipStream_t st, const __half **xs);
 
 // Batch size from which a layer's kernels run on the matrix cores: 4, and already 3 for rows
 // longer than 4096 (measured at batch 3: OPT-30B shape 1 001 against 925 tokens/s, LLaMA-13B
@@ -309,18 +324,27 @@ pf_status launch_hidden(pf_ctx *ctx, const pf_layer *L, const float *x, const fl
     if (pred_mfma(ctx, D, D.d, B) && (size_t)B * (size_t)D.d > (size_t)ctx->hidden_mfma_min_elems) {
         // a batch on the matrix cores; the glue, if any, as a kernel of its own in front
         if (glue_y) {
-            pf_status s = launch_glue(ctx, x, glue_y, glue_ny, D.d, B, x_new, st);
+            pf_status s = launch_glue(ctx, x, glue_y, glue_ny, D.d, B, x_new, st, true);
             if (s != PF_OK) return s;
             x = x_new;
         }
+        const __half *xs = nullptr;  // the activations as fp16 hi + lo planes where possible
+        pf_status s = ensure_split(ctx, x, B, D.d, st, &xs);
+        if (s != PF_OK) return s;
         ProfScope ps(ctx, K_PRED_HIDDEN);
-        PF_LAUNCH(ps, (pf::k_rows_mfma<8, 512, 0>), dim3(cdiv(D.r, 8)), dim3(pf::kMfmaThreads),
-                  (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p1, x, B, D.d, D.r,
-                  (const float *)nullptr, 0.f, ctx->t, (uint64_t *)nullptr, 0, skip);
+        if (xs)
+            PF_LAUNCH(ps, (pf::k_rows_mfma<8, 512, 0, true>), dim3(cdiv(D.r, 8)), dim3(pf::kMfmaThreads),
+                      (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p1, (const void *)xs, B, D.d, D.r,
+                      (const float *)nullptr, 0.f, ctx->t, (uint64_t *)nullptr, 0, skip);
+        else
+            PF_LAUNCH(ps, (pf::k_rows_mfma<8, 512, 0, false>), dim3(cdiv(D.r, 8)), dim3(pf::kMfmaThreads),
+                      (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p1, (const void *)x, B, D.d, D.r,
+                      (const float *)nullptr, 0.f, ctx->t, (uint64_t *)nullptr, 0, skip);
         PF_HIP(ctx, hipGetLastError());
         return PF_OK;
     }
     // hidden layer, in batch tiles that fit LDS
+    if (glue_y && ctx->split_src == x_new) ctx->split_src = nullptr;  // x_new is rewritten as fp32 only
     const int tile = batch_tile(ctx, D.d, B, 1024);
     for (int b0 = 0; b0 < B; b0 += tile) {
         const int bt = (B - b0) < tile ? (B - b0) : tile;
@@ -364,8 +388,8 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
     const __half *p2 = static_cast<const __half *>(L->w.p2);
     if (pred_mfma(ctx, D, D.r, B)) {
         ProfScope ps(ctx, K_PRED_OUT);
-        PF_LAUNCH(ps, (pf::k_rows_mfma<64, 64, 1>), dim3(pred_out_words(L)), dim3(pf::kMfmaThreads),
-                  (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p2, (const float *)ctx->t, B, D.r,
+        PF_LAUNCH(ps, (pf::k_rows_mfma<64, 64, 1, false>), dim3(pred_out_words(L)), dim3(pf::kMfmaThreads),
+                  (size_t)pf::kMfmaWaves * pf::kRowsMfmaSlotBytes, st, p2, (const void *)ctx->t, B, D.r,
                   D.ffn, L->w.p_bias, L->thr_logit, scores, mask_words, L->always_on / 64, skip);
         PF_HIP(ctx, hipGetLastError());
         return PF_OK;
@@ -502,10 +526,21 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
         // 7 us, so two rounds of smaller blocks lose more than their longer chunks gain
         const int grid = ctx->mfma_grid > 0 ? ctx->mfma_grid : ctx->num_cu;
         ProfScope ps(ctx, K_UP_MFMA);
-#define PF_UPM(ACT, FM)                                                                           \
-    PF_LAUNCH(ps, (pf::k_up_mfma<ACT, FM>), dim3(grid), dim3(pf::kMfmaThreads), mfma_lds, st, w_up, \
-              w_gate, L->w.b_up, x, B, idx_in, count_in, mask_words, ctx->idx, ctx->count, ctx->h, \
-              pf::h_stride(B), D.d, D.ffn, up_floor_of(D))
+        // the activations as split planes where this call has them already (the glue kernel or
+        // the matrix-core hidden layer in front made them), else as fp32 values
+        const __half *xs = split_of(ctx, x);
+        const void *xop = xs ? (const void *)xs : (const void *)x;
+#define PF_UPM(ACT, FM)                                                                            \
+    do {                                                                                           \
+        if (xs)                                                                                    \
+            PF_LAUNCH(ps, (pf::k_up_mfma<ACT, FM, true>), dim3(grid), dim3(pf::kMfmaThreads), mfma_lds, \
+                      st, w_up, w_gate, L->w.b_up, xop, B, idx_in, count_in, mask_words, ctx->idx, \
+                      ctx->count, ctx->h, pf::h_stride(B), D.d, D.ffn, up_floor_of(D));            \
+        else                                                                                       \
+            PF_LAUNCH(ps, (pf::k_up_mfma<ACT, FM, false>), dim3(grid), dim3(pf::kMfmaThreads), mfma_lds, \
+                      st, w_up, w_gate, L->w.b_up, xop, B, idx_in, count_in, mask_words, ctx->idx, \
+                      ctx->count, ctx->h, pf::h_stride(B), D.d, D.ffn, up_floor_of(D));            \
+    } while (0)
         if (gated && from_mask) { PF_UPM(1, true); }
         else if (gated) { PF_UPM(1, false); }
         else if (from_mask) { PF_UPM(0, true); }
@@ -632,17 +667,53 @@ pf_status launch_layer_fused(pf_ctx *ctx, const pf_layer *L, const float *x, con
     return PF_OK;
 }
 
+// split: also leave x_next as fp16 hi + lo planes for the matrix-core kernels (split_of(x_next)).
 pf_status launch_glue(pf_ctx *ctx, const float *x, const float *y, int ny, int d, int B,
-                      float *x_next, hipStream_t st)
+                      float *x_next, hipStream_t st, bool split)
 {
+    __half *xs = nullptr;
+    if (split && d % 4 == 0 && ctx->xsplit[0] != nullptr && !ctx->split_off) {
+        ctx->split_cur ^= 1;
+        xs = ctx->xsplit[ctx->split_cur];
+        ctx->split_src = x_next;
+    } else if (ctx->split_src == x_next) {
+        ctx->split_src = nullptr;  // its planes go stale
+    }
     {
         ProfScope ps(ctx, K_GLUE);
         if (d <= pf::kGlueMaxD && d % 4 == 0)
-            PF_LAUNCH(ps, pf::k_glue, dim3(B), dim3(pf::kGlueThreads), 0, st, x, y, ny, x_next, d);
+            PF_LAUNCH(ps, pf::k_glue, dim3(B), dim3(pf::kGlueThreads), 0, st, x, y, ny, x_next, d, xs);
         else
-            PF_LAUNCH(ps, pf::k_glue_long, dim3(B), dim3(pf::kGlueThreads), 0, st, x, y, ny, x_next, d);
+            PF_LAUNCH(ps, pf::k_glue_long, dim3(B), dim3(pf::kGlueThreads), 0, st, x, y, ny, x_next, d, xs);
     }
     PF_HIP(ctx, hipGetLastError());
+    return PF_OK;
+}
+
+// The split planes of x if this call has produced them already, else null.
+const __half *split_of(const pf_ctx *ctx, const float *x)
+{
+    return (x != nullptr && !ctx->split_off && ctx->split_src == x) ? ctx->xsplit[ctx->split_cur] : nullptr;
+}
+
+// The split planes of x, produced by a small kernel if this call has not made them yet.
+pf_status ensure_split(pf_ctx *ctx, const float *x, int B, int d, hipStream_t st, const __half **xs)
+{
+    *xs = split_of(ctx, x);
+    if (*xs) return PF_OK;
+    // no planes: a context without the buffers, an odd shape, or kernels being enqueued on a
+    // second stream (the planes' bookkeeping follows one stream); the caller reads fp32 then
+    if (!ctx->xsplit[0] || (B * d) % 4 != 0 || ctx->split_off) return PF_OK;
+    ctx->split_cur ^= 1;
+    __half *dst = ctx->xsplit[ctx->split_cur];
+    const int n = B * d;
+    {
+        ProfScope ps(ctx, K_GLUE);
+        PF_LAUNCH(ps, pf::k_split, dim3(cdiv(n, 1024)), dim3(256), 0, st, x, dst, n);
+    }
+    PF_HIP(ctx, hipGetLastError());
+    ctx->split_src = x;
+    *xs = dst;
     return PF_OK;
 }
 
@@ -705,7 +776,9 @@ pf_status stack_enqueue_lookahead(pf_ctx *ctx, pf_layer *const *layers, int n_la
     PF_HIP(ctx, hipEventRecord(fork, st));
     PF_HIP(ctx, hipStreamWaitEvent(side, fork, 0));
     auto predict_on_side = [&](int l, const float *seen) -> pf_status {
+        ctx->split_off = true;  // the split planes' bookkeeping follows the main stream only
         pf_status s = launch_predict(ctx, layers[l], seen, nullptr, 0, nullptr, B, nullptr, masks[l & 1], side);
+        ctx->split_off = false;
         if (s != PF_OK) return s;
         PF_HIP(ctx, hipEventRecord(ev_mask(l), side));
         return PF_OK;
@@ -807,6 +880,7 @@ pf_status stack_enqueue_lookahead_merged(pf_ctx *ctx, pf_layer *const *layers, i
         const bool gated = D.act != PF_ACT_RELU;
         const bool glue = l > 0;
         float *xn = glue ? ctx->xbuf[l & 1] : nullptr;
+        if (glue && ctx->split_src == xn) ctx->split_src = nullptr;  // rewritten as fp32 only
         const int n_hid = N ? cdiv(N->desc.r, pf::kPredWaves) : 0;
         int n_up = cdiv(D.ffn, pf::kUpWaves);
         // Measured on the benchmark shapes (batch 1..3): the roles with the dependent chains
@@ -871,7 +945,7 @@ pf_status stack_enqueue_lookahead_merged(pf_ctx *ctx, pf_layer *const *layers, i
 // on the CUs instead of sharing them, and still saves the launch boundary.)
 bool la_merged_mfma_ok(const pf_ctx *ctx, pf_layer *const *layers, int n_layers, int B)
 {
-    if (B < 3 || ctx->lds_budget <= kLdsDefault) return false;
+    if (B < 3 || ctx->lds_budget <= kLdsDefault || !ctx->xsplit[0]) return false;
     for (int l = 0; l < n_layers; ++l) {
         const pf_layer_desc &D = layers[l]->desc;
         if (D.wtype != PF_W_FP16 || B < mfma_from(ctx, D)) return false;
@@ -899,10 +973,13 @@ pf_status stack_enqueue_lookahead_merged_mfma(pf_ctx *ctx, pf_layer *const *laye
         const pf_layer_desc &D = L->desc;
         if (l > 0) {  // the matrix-core kernels read the layer input from memory
             float *xn = ctx->xbuf[l & 1];
-            s = launch_glue(ctx, cur, ctx->ypart, ny, d, B, xn, st);
+            s = launch_glue(ctx, cur, ctx->ypart, ny, d, B, xn, st, true);
             if (s != PF_OK) return s;
             cur = xn;
         }
+        const __half *xs = nullptr;  // both roles of the first launch read the split planes
+        s = ensure_split(ctx, cur, B, d, st, &xs);
+        if (s != PF_OK) return s;
         const int n_hid = N ? cdiv(N->desc.r, 8) : 0;
         const int n_up = ctx->mfma_grid > 0 ? ctx->mfma_grid : ctx->num_cu;
         const bool gated = D.act != PF_ACT_RELU;
@@ -914,7 +991,8 @@ pf_status stack_enqueue_lookahead_merged_mfma(pf_ctx *ctx, pf_layer *const *laye
     PF_LAUNCH(ps, (pf::k_la_up_hidden_mfma<ACT>), dim3(n_up + n_hid), dim3(pf::kMfmaThreads), lds1, st, \
               n_hid, static_cast<const __half *>(N ? N->w.p1 : nullptr), ctx->t, N ? N->desc.r : 0,    \
               static_cast<const __half *>(L->w.w_up), static_cast<const __half *>(L->w.w_gate),        \
-              L->w.b_up, cur, B, (const uint64_t *)masks[l & 1], ctx->idx, ctx->count, ctx->h,         \
+              L->w.b_up, (const void *)xs, B, (const uint64_t *)masks[l & 1], ctx->idx, ctx->count,    \
+              ctx->h,                                                                                  \
               pf::h_stride(B), D.d, D.ffn, up_floor_of(D))
             if (gated)
                 PF_LA1M(1);
@@ -1343,6 +1421,8 @@ pf_status pf_ctx_create(pf_ctx **out, int device, int max_d, int max_ffn, int ma
         PF_ALLOC(ctx->ypart, (size_t)pf::kDown2MaxSplit * max_batch * max_d * sizeof(float));
         PF_ALLOC(ctx->xbuf[0], (size_t)max_batch * max_d * sizeof(float));
         PF_ALLOC(ctx->xbuf[1], (size_t)max_batch * max_d * sizeof(float));
+        PF_ALLOC(ctx->xsplit[0], (size_t)2 * max_batch * max_d * sizeof(__half));
+        PF_ALLOC(ctx->xsplit[1], (size_t)2 * max_batch * max_d * sizeof(__half));
 #undef PF_ALLOC
         e = hipMemset(ctx->count, 0, 64);
         if (e == hipSuccess) {
@@ -1380,6 +1460,8 @@ void pf_ctx_destroy(pf_ctx *ctx)
     (void)hipFree(ctx->count_all);
     (void)hipFree(ctx->h);
     (void)hipFree(ctx->ypart);
+    (void)hipFree(ctx->xsplit[0]);
+    (void)hipFree(ctx->xsplit[1]);
     (void)hipFree(ctx->xbuf[0]);
     (void)hipFree(ctx->xbuf[1]);
     delete ctx;
