@@ -49,6 +49,18 @@ def test_noalloc_layer_step_twice_second_call_smaller(pf):
         assert np.array_equal(y, y_ref)
 
 
+def test_noalloc_on_matrix_cores_same_bits_from_fp32_operands(pf):
+    """Batch 4 with rows of a multiple of 32 elements runs on the matrix cores.  pf_layer_step
+    hands FC1 and the hidden layer the activations as fp16 hi + lo planes written by a small
+    kernel in front; the entry point that allocates nothing has no buffer for the planes and
+    splits inside the kernels.  Both are the same arithmetic: the outputs are equal bit for bit."""
+    for act in (wl.ACT_RELU, wl.ACT_REGLU):
+        cfg = small_cfg(d=2048, ffn=4160, r=256, rate=0.15, act=act)
+        y, y_ref = _both(pf, cfg, 74 + act, 4)
+        assert np.abs(y_ref).max() > 0.1
+        assert np.array_equal(y, y_ref)
+
+
 def test_noalloc_rejects_sizes_beyond_its_limits(pf):
     lib = pf.lib()
     one = ctypes.c_void_p(256)  # never dereferenced: the limits are checked first
