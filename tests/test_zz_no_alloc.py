@@ -55,7 +55,7 @@ def test_noalloc_on_matrix_cores_same_bits_from_fp32_operands(pf):
     kernel in front; the entry point that allocates nothing has no buffer for the planes and
     splits inside the kernels.  Both are the same arithmetic: the outputs are equal bit for bit."""
     for act in (wl.ACT_RELU, wl.ACT_REGLU):
-        cfg = small_cfg(d=2048, ffn=4160, r=256, rate=0.15, act=act)
+        cfg = small_cfg(d=6144, ffn=4160, r=256, rate=0.15, act=act)  # B * d above the hidden layer's matrix-core threshold
         y, y_ref = _both(pf, cfg, 74 + act, 4)
         assert np.abs(y_ref).max() > 0.1
         assert np.array_equal(y, y_ref)
