@@ -232,11 +232,13 @@ pf_status pf_ctx_last_active(pf_ctx *ctx, const uint64_t **mask_words, const int
  * created afterwards take the active set of layer l >= 1 from layer l's predictor applied to
  * the INPUT of layer l-1 (layer 0: its own input), so that the predictor of layer l and the
  * sparse kernels of layer l-1 are independent and a layer costs about max(predictor, sparse
- * FFN) instead of their sum.  With fp16 weights up to batch 3 a layer then runs as two
- * launches whose block ranges play two roles (hidden layer of the next predictor beside FC1;
- * FC2 beside the next predictor's output layer); otherwise the predictors run on a second
- * stream of the library or follow the sparse kernels of the layer before on the same stream,
- * whichever measured faster for the shape.  This changes which neurons are listed
+ * FFN) instead of their sum.  A layer then runs as two launches whose block ranges play two
+ * roles (hidden layer of the next predictor beside FC1; FC2 beside the next predictor's output
+ * layer): stacks of fp16 layers at any batch (vector kernels up to batch 3, matrix-core
+ * kernels above) and stacks of int4 layers up to batch 3.  Other stacks (mixed weight types,
+ * int4 at batch >= 4, row lengths the matrix-core kernels do not take) run the predictors on a
+ * second stream of the library or behind the sparse kernels of the layer before on the same
+ * stream, whichever measured faster for the shape.  This changes which neurons are listed
  * (an approximation whose accuracy depends on trained predictors and is not measured here);
  * every other call is unaffected.  distance: 0 (off, the default) or 1. */
 pf_status pf_ctx_set_lookahead(pf_ctx *ctx, int distance);
