@@ -218,9 +218,7 @@ hipError_t allow_lds_mfma()
     if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<0, true, false>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, false, false>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, true, false>);
-    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<0, false, true>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<0, true, true>);
-    if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, false, true>);
     if (e == hipSuccess) e = allow_lds(pf::k_up_mfma<1, true, true>);
     if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<8, 512, 0, true>);
     if (e == hipSuccess) e = allow_lds(pf::k_rows_mfma<8, 512, 0, false>);
@@ -527,24 +525,20 @@ pf_status launch_sparse(pf_ctx *ctx, const pf_layer *L, const float *x, int B,
         const int grid = ctx->mfma_grid > 0 ? ctx->mfma_grid : ctx->num_cu;
         ProfScope ps(ctx, K_UP_MFMA);
         // the activations as split planes where this call has them already (the glue kernel or
-        // the matrix-core hidden layer in front made them), else as fp32 values
-        const __half *xs = split_of(ctx, x);
+        // the matrix-core hidden layer in front made them; only calls that predict get there),
+        // else as fp32 values
+        const __half *xs = from_mask ? split_of(ctx, x) : nullptr;
         const void *xop = xs ? (const void *)xs : (const void *)x;
-#define PF_UPM(ACT, FM)                                                                            \
-    do {                                                                                           \
-        if (xs)                                                                                    \
-            PF_LAUNCH(ps, (pf::k_up_mfma<ACT, FM, true>), dim3(grid), dim3(pf::kMfmaThreads), mfma_lds, \
-                      st, w_up, w_gate, L->w.b_up, xop, B, idx_in, count_in, mask_words, ctx->idx, \
-                      ctx->count, ctx->h, pf::h_stride(B), D.d, D.ffn, up_floor_of(D));            \
-        else                                                                                       \
-            PF_LAUNCH(ps, (pf::k_up_mfma<ACT, FM, false>), dim3(grid), dim3(pf::kMfmaThreads), mfma_lds, \
-                      st, w_up, w_gate, L->w.b_up, xop, B, idx_in, count_in, mask_words, ctx->idx, \
-                      ctx->count, ctx->h, pf::h_stride(B), D.d, D.ffn, up_floor_of(D));            \
-    } while (0)
-        if (gated && from_mask) { PF_UPM(1, true); }
-        else if (gated) { PF_UPM(1, false); }
-        else if (from_mask) { PF_UPM(0, true); }
-        else { PF_UPM(0, false); }
+#define PF_UPM(ACT, FM, XSV)                                                                          \
+    PF_LAUNCH(ps, (pf::k_up_mfma<ACT, FM, XSV>), dim3(grid), dim3(pf::kMfmaThreads), mfma_lds, st, w_up, \
+              w_gate, L->w.b_up, xop, B, idx_in, count_in, mask_words, ctx->idx, ctx->count, ctx->h,   \
+              pf::h_stride(B), D.d, D.ffn, up_floor_of(D))
+        if (xs && gated) { PF_UPM(1, true, true); }
+        else if (xs) { PF_UPM(0, true, true); }
+        else if (gated && from_mask) { PF_UPM(1, true, false); }
+        else if (gated) { PF_UPM(1, false, false); }
+        else if (from_mask) { PF_UPM(0, true, false); }
+        else { PF_UPM(0, false, false); }
 #undef PF_UPM
     }
     for (int b0 = 0; b0 < B && !mfma; b0 += tile) {
