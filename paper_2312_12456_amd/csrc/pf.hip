@@ -410,7 +410,9 @@ pf_status launch_predict(pf_ctx *ctx, const pf_layer *L, const float *x, const f
 // workgroups share a CU at about 1.6 x the time of one while the batch is small enough for two
 // to be resident (measured at 112 and 128 tiles; at batch 8 the second workgroup waits); more
 // rounds cost a round each.  Ties go to the smaller P (fewer partial sums to add).
-inline int fc2_split(const pf_ctx *ctx, int tiles, int B)
+// two_per_cu = false: one round only (FC2 over segments, whose workgroups carry more state;
+// measured at the OPT-30B and Falcon-40B shapes at batch 2: 776 against 752, 638 against 628).
+inline int fc2_split(const pf_ctx *ctx, int tiles, int B, bool two_per_cu = true)
 {
     if (ctx->down_split > 0) return ctx->down_split < pf::kDown2MaxSplit ? ctx->down_split : pf::kDown2MaxSplit;
     int best = 1;
@@ -420,7 +422,7 @@ inline int fc2_split(const pf_ctx *ctx, int tiles, int B)
         double rounds;
         if (blocks <= ctx->num_cu)
             rounds = 1.0;
-        else if (B <= 4 && blocks <= 2 * ctx->num_cu)
+        else if (two_per_cu && B <= 4 && blocks <= 2 * ctx->num_cu)
             rounds = 1.6;
         else
             rounds = (double)cdiv(blocks, ctx->num_cu);
@@ -643,7 +645,7 @@ pf_status launch_layer_fused(pf_ctx *ctx, const pf_layer *L, const float *x, con
 #undef PF_OU
     }
     const int tiles = cdiv(D.d, pf::kDown2Cols);
-    const int P = fc2_split(ctx, tiles, B);
+    const int P = fc2_split(ctx, tiles, B, false);
     {
         ProfScope ps(ctx, K_DOWN_MASK);
         const bool multi = cdiv(D.ffn / 64, 8 * P) > pf::down2m_batch(B);
@@ -910,6 +912,10 @@ pf_status stack_enqueue_lookahead_merged(pf_ctx *ctx, pf_layer *const *layers, i
         int P = ctx->down_split > 0 ? ctx->down_split : ctx->num_cu / tiles;
         if (P < 1) P = 1;
         if (ctx->down_split == 0 && P > 2) P = 2;
+        // a single row group where the output layer beside it streams long enough to cover it
+        // (measured: OPT-30B shape, 88 MB, +2 % at batch 1 and +4 % at batch 2; Falcon-40B shape,
+        // 67 MB, even; OPT-6.7B shape, 34 MB, -10 %): the next launch then reads one vector less
+        if (ctx->down_split == 0 && N && (size_t)2 * N->desc.ffn * N->desc.r >= (size_t)80000000) P = 1;
         if (P > pf::kDown2MaxSplit) P = pf::kDown2MaxSplit;
         const int n_out = N ? (N->desc.ffn - N->always_on) / pf::kLaOutNeurons : 0;
         const size_t lds2 = N ? ((size_t)B * kpad_of(N->desc.r) + pf::kStageScrap) * sizeof(float) : 0;
