@@ -129,6 +129,47 @@ def test_stack_lookahead_over_int4_layers_matches_oracle(pf, act, B):
     _lookahead_case(pf, act, B, d=640, r=136, two_launch=B <= 3, wtype=wl.W_INT4_G128)
 
 
+@pytest.mark.parametrize("family", ["vector", "matrix-cores", "int4"])
+@pytest.mark.parametrize("threshold", [1e-6, 1.0 - 1e-6])
+def test_stack_lookahead_with_every_or_no_neuron_active(pf, family, threshold):
+    """The degenerate lists through the two-launch look-ahead forms: a threshold below every score
+    lists all 1344 neurons in every layer (FC1's shares and FC2's rounds at their longest), one
+    above every score lists none (FC1 and FC2 have nothing to do: the output is the glue of the
+    bias-only FFN).  Sets bit exact, output within the bar, against the oracle's look-ahead stack."""
+    from oracle import pf_oracle
+    if family == "matrix-cores":
+        cfg, B = small_cfg(d=512, ffn=1344, r=128, rate=0.1, layers=3), 5
+    elif family == "int4":
+        cfg, B = small_cfg(d=640, ffn=1344, r=136, rate=0.1, layers=3, wtype=wl.W_INT4_G128), 2
+    else:
+        cfg, B = small_cfg(d=520, ffn=1344, r=136, rate=0.1, layers=3), 2
+    cfg = wl.scaled(cfg, threshold=threshold)
+    lays = [wl.make_layer(cfg, l, 91, device="cuda") for l in range(cfg.layers)]
+    Os = [oracle_layer(cfg, wl.to_host(t)) for t in lays]
+    x = wl.make_inputs(cfg, 0, seed=91, batch=B, device="cuda")
+    ref, masks = pf_oracle.stack_lookahead(Os, x.cpu().numpy())
+    want_all = threshold < 0.5
+    for m in masks:
+        assert m.all() if want_all else not m.any()   # the scores stay clear of such thresholds
+    ctx = pf.Context(cfg.d, cfg.ffn, cfg.r, max_batch=B)
+    Ls = [pf.Layer.from_workload(ctx, cfg, t) for t in lays]
+    ctx.set_lookahead(1)
+    trace = MaskTrace(ctx, cfg.layers, cfg.ffn)
+    out = torch.full_like(x, float("nan"))
+    ctx.profile_begin()
+    ctx.stack_step(Ls, x, out)
+    stats = ctx.profile_end()
+    torch.cuda.synchronize()
+    ctx.set_mask_trace(None)
+    assert stats["k_la_up_hidden"][0] == cfg.layers and stats["k_la_down_out"][0] == cfg.layers, stats
+    for l, m in enumerate(trace.masks()):
+        assert np.array_equal(m, masks[l]), "layer %d" % l
+    check_output(out.cpu().numpy(), ref, "look-ahead stack, %s, threshold %g" % (family, threshold))
+    _, lst = _last_list(pf, ctx, cfg.ffn)
+    assert lst.size == (cfg.ffn if want_all else 0)
+    assert np.array_equal(lst, np.flatnonzero(masks[-1]))
+
+
 def _lookahead_case(pf, act, B, d, r, two_launch, wtype=wl.W_FP16):
     """Look-ahead prediction at distance 1 through pf_stack_step and a recorded plan against the
     oracle's look-ahead stack, in both forms the library has: two launches per layer whose block
