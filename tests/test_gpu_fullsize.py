@@ -143,7 +143,7 @@ def test_full_shape_stack_three_launch_form_matches_oracle(pf, oracle, name, B):
 
 @pytest.mark.parametrize("name,B", [("opt-6.7b", 1), ("opt-6.7b", 3), ("llama2-13b-reglu", 2), ("opt-30b", 2),
                                     # the same form from the matrix-core kernels ...
-                                    ("opt-30b", 4), ("opt-30b", 8), ("llama2-13b-reglu", 4),
+                                    ("opt-30b", 3), ("opt-30b", 4), ("opt-30b", 8), ("llama2-13b-reglu", 4),
                                     ("bamboo-7b-drelu", 4),
                                     # ... and from the int4 kernels
                                     ("opt-175b-int4", 1)])
