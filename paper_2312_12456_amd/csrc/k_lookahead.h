@@ -12,7 +12,9 @@
 // stream on this part (graph branches replay one after the other), but workgroups of two roles
 // share the CUs.  Inside a stack both roles of the first launch form the layer input from the
 // previous layer's input and FC2 partial sums themselves (GLUE); FC1's first block stores it.
-// The role bodies are the stand-alone kernels' own.
+// The role bodies are the stand-alone kernels' own.  Three families: the vector kernels (fp16,
+// batch <= 3; below), the matrix-core kernels (fp16, larger batches) and the int4 kernels
+// (further down; those two read a layer input that a glue kernel in front has formed).
 #pragma once
 #include "dev_util.h"
 #include "k_predict.h"
